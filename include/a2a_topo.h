@@ -1,0 +1,160 @@
+/*
+ * a2a_topo -- all-to-all evaluation of a direct-connect topology on one AMD MI355X.
+ *
+ * The topology is the directed graph G=(V,E) of Sec. 2.2 of the paper (|V| = N hosts,
+ * out-degree d, link bandwidth b), handed over as an int32 out-neighbour CSR.  Every CSR
+ * entry is one link; its position is the link id.  The library computes, entirely in HIP
+ * kernels on the device:
+ *   - hop distances D(s,t) (the D(.,.) of Theorem 1, Sec. 5.4) and the number sigma(s,t)
+ *     of distinct shortest link sequences ("all the shortest paths", Sec. 5.2);
+ *   - the Equal-weight Shortest Path (EwSP) link loads of Sec. 5.2 / 5.3: every ordered
+ *     pair carries unit demand, split equally over all of its shortest paths;
+ *   - the schedule figures that follow: all-to-all time = maximum link load (Sec. 5.3)
+ *     scaled by m/b, the capacity lower bound of Eq. (lb) (Theorem 1), throughput
+ *     (N-1)m/T (Sec. 2.2) and its upper bound (N-1) f b (Sec. 5.1).
+ *
+ * Conventions
+ *   - "host" / "device" after a pointer says where the memory lives.  The caller owns every
+ *     buffer and the stream; the library owns only the opaque handle (a device copy of the
+ *     out- and in-neighbour CSR, a few KB of pinned host memory).
+ *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  a2a_distances and a2a_link_loads wait on that stream once per BFS
+ *     level (the number of levels is data dependent) and return with the remaining work
+ *     enqueued; a2a_schedule_bound waits for its result.
+ *   - Every function returns an a2a_status (0 = A2A_OK, negative = error); nothing throws,
+ *     aborts or prints.  On error the outputs are unspecified.
+ *   - Sources are processed in batches of 64 (one bit of a 64-bit mask per source); several
+ *     batches advance level by level together, as many as the workspace holds.
+ */
+#ifndef A2A_TOPO_H
+#define A2A_TOPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct a2a_topo a2a_topo;
+
+typedef enum a2a_status {
+  A2A_OK = 0,
+  A2A_ERR_INVALID_ARG = -1,         /* null pointer, N <= 0, malformed CSR, bad source range */
+  A2A_ERR_SELF_LOOP = -2,           /* a link u -> u (generators drop them before create) */
+  A2A_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace cannot hold one batch of 64 sources */
+  A2A_ERR_HIP = -4,                 /* a HIP runtime call failed (no device, out of memory ...) */
+  A2A_ERR_NOT_IMPLEMENTED = -5,
+  A2A_ERR_DISCONNECTED = -6,        /* some ordered pair has no path: all-to-all infeasible */
+  A2A_ERR_NO_MEMORY = -7,           /* host allocation failed */
+  A2A_ERR_LEVEL_OVERFLOW = -8       /* BFS went deeper than the level bound of the handle */
+} a2a_status;
+
+/* flags of a2a_workspace_bytes */
+#define A2A_WS_DISTANCES 0x0 /* a2a_distances without sigma */
+#define A2A_WS_SIGMA 0x1     /* a2a_distances with sigma */
+#define A2A_WS_LOADS 0x2     /* a2a_link_loads */
+#define A2A_WS_MINIMAL 0x100 /* smallest usable size (one batch at a time) instead of the
+                                recommended one (all batches advance together) */
+
+/* bits written to *flags by a2a_distances / a2a_link_loads */
+#define A2A_FLAG_SIGMA_INEXACT 0x1 /* some path count reached 2^53: sigma no longer exact */
+#define A2A_FLAG_UNREACHABLE 0x2   /* some ordered pair (s,t), t != s, has no path */
+
+/*
+ * Validates the CSR, builds the in-neighbour CSR (stable in link-id order) and uploads both.
+ *   N        number of hosts, > 0
+ *   row_ptr  host, int32[N+1], row_ptr[0] = 0, non-decreasing, row_ptr[N] = E (E may be 0)
+ *   col_idx  host, int32[E], each in [0,N); parallel links allowed, self-loops rejected
+ *   out      receives the handle; release with a2a_topo_destroy
+ * Validation happens before the first HIP call, so malformed input is reported as
+ * A2A_ERR_INVALID_ARG / A2A_ERR_SELF_LOOP even on a machine without a GPU.
+ * The handle also records a level bound: an upper bound on the largest finite D(s,t)
+ * (eccentricities of node 0 in both directions if G is strongly connected, else N-1).
+ */
+int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a2a_topo** out);
+
+/* Frees the handle and its device memory.  NULL is ignored. */
+void a2a_topo_destroy(a2a_topo* topo);
+
+/* Any output pointer may be NULL.  dmax = largest out-degree. */
+int a2a_topo_info(const a2a_topo* topo, int32_t* N, int64_t* E, int32_t* dmax, int32_t* level_bound);
+
+/*
+ * Bytes of device workspace for a call over src_count sources.  With A2A_WS_MINIMAL the
+ * smallest size the call accepts; otherwise the size at which all ceil(src_count/64) batches
+ * advance together (fewest kernel launches).  Any size in between is used as well as it can
+ * be.  Returns 0 on bad arguments.  The workspace must be 256-byte aligned.
+ */
+size_t a2a_workspace_bytes(const a2a_topo* topo, int32_t src_count, int flags);
+
+/*
+ * Hop distances (and optionally shortest-path counts) from sources
+ * src_begin .. src_begin+src_count-1 to every node: D(s,t) of Theorem 1 (Sec. 5.4) by
+ * bit-parallel breadth-first search, sigma(s,t) by level-ordered accumulation over the
+ * links that lie on shortest paths (Sec. 5.2).
+ *   dist         device, int32[src_count][N], row-major; -1 = unreachable.  May be NULL.
+ *   sigma        device, double[src_count][N]; exact integers below 2^53, 0 = unreachable.
+ *                May be NULL (then no path counting is done).
+ *   dist_sum     device, int64[src_count]: sum_t D(s,t) over reachable t.  May be NULL.
+ *   unreachable  device, int64[1]: number of pairs (s,t), t != s, without a path. May be NULL.
+ *   flags        device, int64[1]: A2A_FLAG_* bits.  May be NULL.
+ *   workspace    device, workspace_bytes bytes (see a2a_workspace_bytes), 256-byte aligned
+ */
+int a2a_distances(const a2a_topo* topo, int32_t src_begin, int32_t src_count, int32_t* dist,
+                  double* sigma, int64_t* dist_sum, int64_t* unreachable, int64_t* flags,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * EwSP link loads (Sec. 5.2, Sec. 5.3) of the unit demands whose source lies in
+ * src_begin .. src_begin+src_count-1 (0, N = the full all-to-all):
+ *   load[a] = sum_s sum_{t != s} (# shortest s->t paths through link a) / sigma(s,t).
+ * Computed per source batch by a forward path-count pass and a backward dependency pass over
+ * the shortest-path DAG; batch results are added in ascending batch order, so the result is
+ * bitwise reproducible for a given workspace size.
+ *   load            device, double[E], overwritten
+ *   dist_sum_total  device, int64[1]: sum over these sources of sum_t D(s,t).  May be NULL.
+ *   flags           device, int64[1]: A2A_FLAG_* bits.  May be NULL.
+ */
+int a2a_link_loads(const a2a_topo* topo, int32_t src_begin, int32_t src_count, double* load,
+                   int64_t* dist_sum_total, int64_t* flags, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+typedef struct a2a_bound {
+  double max_load;         /* Lmax: all-to-all time under unit demand and capacity (Sec. 5.3) */
+  int64_t argmax_arc;      /* lowest link id whose load equals max_load */
+  double min_load;
+  int64_t sum_dist;        /* as passed in */
+  int64_t n_links;         /* E */
+  int32_t n_nodes;         /* N */
+  int32_t dmax;            /* largest out-degree */
+  double t_sched;          /* Lmax * m / b */
+  double t_lb_nd;          /* sum_dist * m / (N * dmax * b): Eq. (lb) summed over all sources */
+  double t_lb_links;       /* sum_dist * m / (E * b): same argument with the true link count */
+  double ratio;            /* t_sched / t_lb_nd */
+  double throughput;       /* (N-1) * m / t_sched (Sec. 2.2) */
+  double flow_value;       /* f = 1 / Lmax (Sec. 5.3) */
+  double throughput_upper; /* (N-1) * f * b (Sec. 5.1) */
+} a2a_bound;
+
+/*
+ * Schedule completion time and bounds from the link loads.
+ *   load       device, double[E] as written by a2a_link_loads over all N sources
+ *   sum_dist   sum over all ordered pairs of D(s,t) (dist_sum_total of that call)
+ *   flags      the A2A_FLAG_* bits of that call; if A2A_FLAG_UNREACHABLE is set the
+ *              function fills `out` and returns A2A_ERR_DISCONNECTED
+ *   m_bytes    shard size m (Sec. 2.2); b_bytes_per_s link bandwidth b.  m = b = 1 gives the
+ *              unit-demand, unit-capacity quantities of Sec. 5.3.
+ *   out        host
+ * The max / argmax / min reduction runs on the device; the function waits for it.
+ */
+int a2a_schedule_bound(const a2a_topo* topo, const double* load, int64_t sum_dist, int64_t flags,
+                       double m_bytes, double b_bytes_per_s, a2a_bound* out, void* hip_stream);
+
+/* Static string for a status code. */
+const char* a2a_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A2A_TOPO_H */

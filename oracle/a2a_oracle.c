@@ -1,0 +1,241 @@
+/*
+ * CPU oracle for the all-to-all topology evaluator.  TEST INFRASTRUCTURE ONLY:
+ * it may be called from tests/, from the smoke check and from the benchmark's
+ * cpu_baseline leg; the product library never links, loads or calls it, and it
+ * shares no code, header or table with the HIP path.
+ *
+ * What it computes (plain definitions, serial per source, fp64 / exact integers):
+ *   D(s,t)      hop distance on the directed topology G=(V,E) of Sec. 2.2, the
+ *               quantity D(.,.) used in the proof of Theorem 1 (Sec. 5.4);
+ *   sigma(s,t)  number of distinct shortest s->t link sequences ("all the
+ *               shortest paths" of the EwSP baseline, Sec. 5.2); every CSR entry
+ *               is its own link, so parallel arcs give distinct paths;
+ *   load[a]     EwSP link load: every ordered pair (s,t) carries unit demand split
+ *               equally over all its shortest paths (Sec. 5.2, Sec. 5.3), so
+ *               load[a] = sum_{s,t} (#shortest s->t paths through a) / sigma(s,t);
+ *   bound       all-to-all time = maximum link load under unit demand and capacity
+ *               (Sec. 5.3), the capacity lower bound sum D / (N d) from Eq. (lb)
+ *               of Theorem 1 summed over all sources, and the throughput formulas
+ *               (N-1) m / T (Sec. 2.2) and (N-1) f b (Sec. 5.1).
+ *
+ * Method: queue BFS from each source over the out-neighbour CSR, path counts
+ * accumulated in BFS order, then the dependency recursion walked in reverse BFS
+ * order (a node's successors on shortest paths are one level deeper, hence final
+ * when it is visited).  Threads only split the source range; each owns a private
+ * load vector and the vectors are merged in thread order.
+ *
+ * Pins (tests/test_oracle_*.py): torus / hypercube / K4,4 closed forms, the
+ * 3x3x3-torus flow value 1/9 of Sec. 5.1, flow-conservation and level-cut
+ * invariants, exact brute-force path enumeration for N <= 12.
+ */
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define A2A_ORACLE_SIGMA_LIMIT (1ULL << 53)
+
+/* Scratch for one source. */
+typedef struct {
+  int32_t* dist;   /* [N]  -1 = unreachable */
+  uint64_t* sigma; /* [N] */
+  double* delta;   /* [N] */
+  int32_t* order;  /* [N] BFS visiting order, doubles as the FIFO queue */
+} src_scratch;
+
+/*
+ * One source.  Fills sc->dist / sc->sigma, adds this source's contribution to
+ * load[] (if non-NULL).  Returns sum_t D(s,t) over reachable t; *reached gets the
+ * number of reachable nodes other than s; *overflow is set when a path count
+ * reaches 2^53 (no longer exact in fp64).
+ */
+static int64_t one_source(int32_t N, const int32_t* row_ptr, const int32_t* col, int32_t s,
+                          src_scratch* sc, double* load, int64_t* reached, int* overflow) {
+  int32_t head = 0, tail = 0;
+  int64_t dsum = 0;
+  for (int32_t v = 0; v < N; ++v) {
+    sc->dist[v] = -1;
+    sc->sigma[v] = 0;
+    sc->delta[v] = 0.0;
+  }
+  sc->dist[s] = 0;
+  sc->sigma[s] = 1;
+  sc->order[tail++] = s;
+  while (head < tail) {
+    int32_t u = sc->order[head++];
+    for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) {
+      int32_t w = col[a];
+      if (sc->dist[w] < 0) {
+        sc->dist[w] = sc->dist[u] + 1;
+        dsum += sc->dist[w];
+        sc->order[tail++] = w;
+      }
+      if (sc->dist[w] == sc->dist[u] + 1) {
+        sc->sigma[w] += sc->sigma[u];
+        if (sc->sigma[w] >= A2A_ORACLE_SIGMA_LIMIT) *overflow = 1;
+      }
+    }
+  }
+  *reached = (int64_t)tail - 1;
+  if (load) {
+    for (int32_t i = tail - 1; i >= 0; --i) {
+      int32_t u = sc->order[i];
+      for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) {
+        int32_t w = col[a];
+        if (sc->dist[w] == sc->dist[u] + 1) {
+          /* share of the traffic arriving at (and destined to) w that came over link a */
+          double c = (double)sc->sigma[u] / (double)sc->sigma[w] * (1.0 + sc->delta[w]);
+          load[a] += c;
+          sc->delta[u] += c;
+        }
+      }
+    }
+  }
+  return dsum;
+}
+
+typedef struct {
+  int32_t N;
+  const int32_t* row_ptr;
+  const int32_t* col;
+  int32_t s_begin, s_end; /* this thread's sources */
+  int32_t s_base;         /* first source of the whole call (row 0 of the outputs) */
+  int32_t* dist_out;
+  uint64_t* sigma_out;
+  double* load;           /* private [E] or NULL */
+  int64_t* dist_sum;
+  int64_t unreachable;
+  int overflow;
+  int failed;
+} job;
+
+static void* worker(void* p) {
+  job* j = (job*)p;
+  int32_t N = j->N;
+  src_scratch sc;
+  sc.dist = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  sc.sigma = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)N);
+  sc.delta = (double*)malloc(sizeof(double) * (size_t)N);
+  sc.order = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  if (!sc.dist || !sc.sigma || !sc.delta || !sc.order) {
+    j->failed = 1;
+  } else {
+    for (int32_t s = j->s_begin; s < j->s_end; ++s) {
+      int64_t reached = 0;
+      int64_t ds = one_source(N, j->row_ptr, j->col, s, &sc, j->load, &reached, &j->overflow);
+      size_t row = (size_t)(s - j->s_base);
+      if (j->dist_sum) j->dist_sum[row] = ds;
+      j->unreachable += (int64_t)(N - 1) - reached;
+      if (j->dist_out) memcpy(j->dist_out + row * (size_t)N, sc.dist, sizeof(int32_t) * (size_t)N);
+      if (j->sigma_out) memcpy(j->sigma_out + row * (size_t)N, sc.sigma, sizeof(uint64_t) * (size_t)N);
+    }
+  }
+  free(sc.dist);
+  free(sc.sigma);
+  free(sc.delta);
+  free(sc.order);
+  return NULL;
+}
+
+/*
+ * Sources src_begin .. src_begin+src_count-1 of the topology given as an
+ * out-neighbour CSR.  Outputs (each may be NULL): dist_out / sigma_out are
+ * [src_count][N]; load is [E] and is overwritten with the sum over these sources;
+ * dist_sum is [src_count]; *unreachable counts ordered pairs (s,t), t != s, with
+ * no path; *flags bit0 = some sigma >= 2^53, bit1 = some pair unreachable.
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int a2a_oracle_run(int32_t N, const int32_t* row_ptr, const int32_t* col, int32_t src_begin,
+                   int32_t src_count, int32_t threads, int32_t* dist_out, uint64_t* sigma_out,
+                   double* load, int64_t* dist_sum, int64_t* unreachable, int64_t* flags) {
+  if (N <= 0 || !row_ptr || src_begin < 0 || src_count < 0 || src_begin + (int64_t)src_count > N)
+    return -1;
+  int64_t E = row_ptr[N];
+  if (E > 0 && !col) return -1;
+  if (threads < 1) threads = 1;
+  if (threads > src_count) threads = src_count > 0 ? src_count : 1;
+  job* jobs = (job*)calloc((size_t)threads, sizeof(job));
+  pthread_t* tid = (pthread_t*)calloc((size_t)threads, sizeof(pthread_t));
+  if (!jobs || !tid) return -1;
+  int rc = 0;
+  for (int t = 0; t < threads; ++t) {
+    job* j = &jobs[t];
+    j->N = N;
+    j->row_ptr = row_ptr;
+    j->col = col;
+    j->s_base = src_begin;
+    j->s_begin = src_begin + (int32_t)(((int64_t)src_count * t) / threads);
+    j->s_end = src_begin + (int32_t)(((int64_t)src_count * (t + 1)) / threads);
+    j->dist_out = dist_out;
+    j->sigma_out = sigma_out;
+    j->dist_sum = dist_sum;
+    if (load) {
+      j->load = (double*)calloc((size_t)(E > 0 ? E : 1), sizeof(double));
+      if (!j->load) rc = -1;
+    }
+  }
+  if (rc == 0) {
+    for (int t = 1; t < threads; ++t) pthread_create(&tid[t], NULL, worker, &jobs[t]);
+    worker(&jobs[0]);
+    for (int t = 1; t < threads; ++t) pthread_join(tid[t], NULL);
+  }
+  int64_t unr = 0, fl = 0;
+  if (load) memset(load, 0, sizeof(double) * (size_t)E);
+  for (int t = 0; t < threads; ++t) {
+    if (jobs[t].failed) rc = -1;
+    unr += jobs[t].unreachable;
+    if (jobs[t].overflow) fl |= 1;
+    if (load && jobs[t].load)
+      for (int64_t a = 0; a < E; ++a) load[a] += jobs[t].load[a];
+    free(jobs[t].load);
+  }
+  if (unr) fl |= 2;
+  if (unreachable) *unreachable = unr;
+  if (flags) *flags = fl;
+  free(jobs);
+  free(tid);
+  return rc;
+}
+
+/*
+ * Schedule figures from the link loads.  out[] (10 doubles):
+ *  0 max link load Lmax          (all-to-all time under unit demand/capacity, Sec. 5.3)
+ *  1 lowest link id attaining it
+ *  2 min link load
+ *  3 t_sched   = Lmax * m / b
+ *  4 t_lb_nd   = sumD * m / (N * dmax * b)   (Eq. (lb): demand sum D against capacity N d)
+ *  5 t_lb_links= sumD * m / (E * b)          (same argument with the true link count)
+ *  6 ratio     = t_sched / t_lb_nd
+ *  7 throughput= (N-1) m / t_sched           (Sec. 2.2)
+ *  8 f         = 1 / Lmax                    (concurrent flow value the loads realise)
+ *  9 upper     = (N-1) f b                   (Sec. 5.1)
+ */
+int a2a_oracle_bound(int32_t N, const int32_t* row_ptr, const double* load, int64_t sum_dist,
+                     double m, double b, double* out) {
+  if (N <= 0 || !row_ptr || !out) return -1;
+  int64_t E = row_ptr[N];
+  if (E <= 0 || !load) return -1;
+  int32_t dmax = 0;
+  for (int32_t u = 0; u < N; ++u)
+    if (row_ptr[u + 1] - row_ptr[u] > dmax) dmax = row_ptr[u + 1] - row_ptr[u];
+  double lmax = load[0], lmin = load[0];
+  int64_t arg = 0;
+  for (int64_t a = 1; a < E; ++a) {
+    if (load[a] > lmax) {
+      lmax = load[a];
+      arg = a;
+    }
+    if (load[a] < lmin) lmin = load[a];
+  }
+  out[0] = lmax;
+  out[1] = (double)arg;
+  out[2] = lmin;
+  out[3] = lmax * m / b;
+  out[4] = (double)sum_dist * m / ((double)N * (double)dmax * b);
+  out[5] = (double)sum_dist * m / ((double)E * b);
+  out[6] = out[3] / out[4];
+  out[7] = (double)(N - 1) * m / out[3];
+  out[8] = 1.0 / lmax;
+  out[9] = (double)(N - 1) * out[8] * b;
+  return 0;
+}
