@@ -1,0 +1,206 @@
+"""HIP path vs CPU oracle through the C ABI, element by element (needs an MI355X)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import a2a_inputs as gen
+from helpers import tiny_graphs, GOLDEN
+from gpu_helpers import run_link_loads, run_distances, assert_loads_close, assert_sigma_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def a2a():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2309_13541_amd as lib
+    lib.load_library()
+    return lib
+
+
+SMALL = dict(tiny_graphs())
+SMALL.update({
+    "torus3x3x3": gen.torus([3, 3, 3]),
+    "ring_odd_131": gen.ring(131),              # diameter 130, N not a multiple of 64
+    "biring_200": gen.bidirectional_ring(200),  # diameter 100 = N/2
+    "kautz_81_8": gen.imase_itoh(81, 8),
+    "kautz_100_3": gen.imase_itoh(100, 3),
+    "rr_300_4": gen.random_regular(300, 4, 5),
+    "rr_257_8": gen.random_regular(257, 8, 11),
+    "torus_5x13": gen.torus([5, 13]),           # N = 65: one node into the second batch
+    "hub_in_100": gen.csr_from_rows([[99] for _ in range(99)] + [list(range(99))]),  # degree 99
+    "punctured_333": gen.remove_arcs(gen.torus([3, 3, 3]), [3, 50, 101]),
+    "punctured_nodes_333": gen.remove_nodes(gen.torus([3, 3, 3]), [0, 13, 20]),
+    "two_components": gen.csr_from_rows([[1], [0], [3], [4], [2]]),
+    "no_links": gen.csr_from_rows([[], [], []]),
+    "chain_2pow54": gen.csr_from_rows([[i + 1, i + 1] for i in range(54)] + [[]]),
+})
+
+
+@pytest.mark.parametrize("name", sorted(SMALL))
+def test_small_graphs_everything(a2a, oracle, name):
+    rp, col = SMALL[name]
+    print(f"case {name} N={len(rp) - 1} E={len(col)}", flush=True)
+    o = oracle.run(rp, col, want_dist=True, want_sigma=True)
+    topo = a2a.Topology(rp, col)
+    dist, sigma, dsum, unr, flags = run_distances(topo)
+    assert np.array_equal(dist, o.dist)
+    assert np.array_equal(dsum, o.dist_sum)
+    assert unr == o.unreachable
+    assert flags == o.flags
+    if not (o.flags & 1):
+        assert_sigma_equal(sigma, o.sigma)
+    else:  # counts beyond 2^53 are flagged, and still agree to fp64 rounding
+        np.testing.assert_allclose(sigma, o.sigma.astype(np.float64), rtol=1e-15)
+    load, dtot, lflags = run_link_loads(topo)
+    assert dtot == int(o.dist_sum.sum()) and lflags == o.flags
+    if len(col):
+        assert_loads_close(load, o.load)
+    topo.close()
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4"])
+def test_configs_loads_and_sums(a2a, oracle, name):
+    rp, col = gen.named_config(name)
+    print(f"case {name}", flush=True)
+    o = oracle.run(rp, col, threads=16)
+    topo = a2a.Topology(rp, col)
+    load, dtot, flags = run_link_loads(topo)
+    assert dtot == int(o.dist_sum.sum()) and flags == 0
+    assert_loads_close(load, o.load)
+    if name == "C4":  # unique shortest paths: whole-number loads, exact on both sides
+        assert np.array_equal(load, o.load)
+    # schedule figures against the oracle's formulas
+    b, st = topo.schedule_bound(topo_load_tensor(load), dtot, flags, 2.0 ** 20, 3.125e9)
+    ob = oracle.bound(rp, load, dtot, 2.0 ** 20, 3.125e9)  # same load vector on both sides
+    assert st == 0
+    for k in ("max_load", "min_load", "t_sched", "t_lb_nd", "t_lb_links", "ratio", "throughput",
+              "flow_value", "throughput_upper"):
+        assert getattr(b, k) == pytest.approx(ob[k], rel=1e-14), k
+    assert b.argmax_arc == ob["argmax_arc"]
+    assert b.n_links == len(col) and b.n_nodes == len(rp) - 1 and b.sum_dist == dtot
+    topo.close()
+
+
+def topo_load_tensor(load_np):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(load_np)).cuda()
+
+
+@pytest.mark.parametrize("name,ranges", [
+    ("C1", [(0, 64)]),
+    ("C2", [(0, 1024)]),
+    ("C3", [(0, 300), (4000, 96)]),
+    ("C4", [(0, 130), (9000, 64), (16384 - 70, 70)]),
+    ("C5", [(0, 64), (30000, 100), (65536 - 65, 65)]),
+])
+def test_configs_distances_and_sigma(a2a, oracle, name, ranges):
+    rp, col = gen.named_config(name)
+    topo = a2a.Topology(rp, col)
+    for s0, cnt in ranges:
+        print(f"case {name} sources {s0}+{cnt}", flush=True)
+        o = oracle.run(rp, col, s0, cnt, threads=16, want_dist=True, want_sigma=True, want_load=False)
+        dist, sigma, dsum, unr, flags = run_distances(topo, s0, cnt)
+        assert np.array_equal(dist, o.dist)
+        assert_sigma_equal(sigma, o.sigma)
+        assert np.array_equal(dsum, o.dist_sum)
+        assert unr == 0 and flags == 0
+        # distances alone (no path counting) take another code path
+        dist2, _, dsum2, _, _ = run_distances(topo, s0, cnt, want_sigma=False)
+        assert np.array_equal(dist2, o.dist) and np.array_equal(dsum2, o.dist_sum)
+    topo.close()
+
+
+def test_c5_source_ranges_loads(a2a, oracle):
+    """Loads of sub-ranges of sources at full C5 size, element by element."""
+    rp, col = gen.named_config("C5")
+    topo = a2a.Topology(rp, col)
+    for s0, cnt in [(0, 512), (41000, 200), (65536 - 100, 100)]:
+        print(f"case C5 sources {s0}+{cnt}", flush=True)
+        o = oracle.run(rp, col, s0, cnt, threads=16)
+        load, dtot, flags = run_link_loads(topo, s0, cnt)
+        assert dtot == int(o.dist_sum.sum()) and flags == 0
+        assert_loads_close(load, o.load)
+    topo.close()
+
+
+def test_c5_full_against_stored_oracle_values(a2a, oracle):
+    """Full C5 in the benchmark's launch configuration (recommended workspace): stored oracle
+    figures (sum of distances, extrema, 257 sampled links) plus the load-sum invariant."""
+    with open(os.path.join(GOLDEN, "oracle_config_values.json")) as f:
+        g = json.load(f)["C5"]
+    rp, col = gen.named_config("C5")
+    topo = a2a.Topology(rp, col)
+    print("case C5 full", flush=True)
+    load, dtot, flags = run_link_loads(topo)
+    assert dtot == g["sum_dist"] and flags == 0
+    want = np.array([float.fromhex(x) for x in g["sample_loads"]])
+    assert_loads_close(load[np.asarray(g["sample_ids"])], want)
+    assert float(load.max()) == pytest.approx(float.fromhex(g["max_load"]), rel=1e-9)
+    assert float(load.min()) == pytest.approx(float.fromhex(g["min_load"]), rel=1e-9)
+    assert int(np.argmax(load)) == g["argmax_arc"]
+    assert float(load.sum()) == pytest.approx(float(dtot), rel=1e-10)
+    b, st = topo.schedule_bound(topo_load_tensor(load), dtot, flags)
+    assert st == 0 and b.argmax_arc == g["argmax_arc"]
+    assert b.max_load * b.n_links / dtot == pytest.approx(g["ratio_links"], rel=1e-9)
+    topo.close()
+
+
+def test_workspace_size_does_not_change_results(a2a, oracle):
+    """One batch at a time vs all batches together: same integers, bitwise-same loads."""
+    rp, col = gen.random_regular(1000, 6, 21)
+    topo = a2a.Topology(rp, col)
+    full = run_link_loads(topo)
+    least = topo.workspace_bytes(topo.N, a2a.WS_LOADS | a2a.WS_MINIMAL)
+    one = run_link_loads(topo, max_ws=least)
+    three = run_link_loads(topo, max_ws=3 * least)
+    assert np.array_equal(full[0], one[0]) and np.array_equal(full[0], three[0])
+    assert full[1:] == one[1:] == three[1:]
+    again = run_link_loads(topo)
+    assert np.array_equal(full[0], again[0])  # run-to-run bitwise determinism
+    d_full = run_distances(topo)
+    d_one = run_distances(topo, max_ws=topo.workspace_bytes(topo.N, a2a.WS_SIGMA | a2a.WS_MINIMAL))
+    for x, y in zip(d_full[:3], d_one[:3]):
+        assert np.array_equal(x, y)
+    topo.close()
+
+
+def test_empty_and_partial_source_ranges(a2a, oracle):
+    rp, col = gen.torus([7, 11])
+    topo = a2a.Topology(rp, col)
+    load, dtot, flags = run_link_loads(topo, 5, 0)
+    assert np.all(load == 0) and dtot == 0 and flags == 0
+    for s0, cnt in [(0, 1), (76, 1), (3, 64), (10, 67)]:
+        o = oracle.run(rp, col, s0, cnt, want_dist=True, want_sigma=True)
+        load, dtot, flags = run_link_loads(topo, s0, cnt)
+        assert_loads_close(load, o.load)
+        assert dtot == int(o.dist_sum.sum())
+        dist, sigma, dsum, unr, fl = run_distances(topo, s0, cnt)
+        assert np.array_equal(dist, o.dist) and np.array_equal(dsum, o.dist_sum)
+        assert_sigma_equal(sigma, o.sigma)
+    topo.close()
+
+
+def test_error_paths_on_device(a2a):
+    import torch
+    rp, col = gen.torus([4, 4])
+    topo = a2a.Topology(rp, col)
+    load = torch.zeros(topo.E, dtype=torch.float64, device="cuda")
+    tiny = torch.empty(512, dtype=torch.uint8, device="cuda")
+    with pytest.raises(a2a.A2AError) as e:
+        topo.link_loads(0, 16, load=load, workspace=tiny)
+    assert e.value.status == a2a.ERR_WORKSPACE_TOO_SMALL
+    ws = topo.alloc_workspace(16, a2a.WS_LOADS)
+    with pytest.raises(a2a.A2AError) as e:
+        topo.link_loads(10, 7, load=load, workspace=ws)
+    assert e.value.status == a2a.ERR_INVALID_ARG
+    # disconnected topology: loads are still produced, schedule_bound reports it
+    t2 = a2a.Topology(*gen.csr_from_rows([[1], [0], [3], [4], [2]]))
+    l2, d2, f2 = run_link_loads(t2)
+    assert f2 & a2a.FLAG_UNREACHABLE
+    b, st = t2.schedule_bound(topo_load_tensor(l2), d2, f2, allow_disconnected=True)
+    assert st == a2a.ERR_DISCONNECTED and b.max_load == 3.0
+    topo.close(); t2.close()
