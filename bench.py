@@ -1,0 +1,170 @@
+"""Benchmark: all-pairs BFS + EwSP link loads on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--cpu-sources S]
+
+One step = one pass of the whole hot path over the topology: a2a_link_loads over all N
+sources (bit-parallel BFS, forward path counts, backward dependency pass, ordered reduction)
+followed by a2a_schedule_bound.  The CSR is resident on the device before the timed region.
+Prints one JSON line.  TEPS = N * E / seconds (one traversed edge = one (source, link) pair).
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(N, E, src, dag_links):
+    """Bytes the method has to move once per-batch state exceeds on-chip storage.
+
+    per (source, node) pair: level tag 1 B written + 1 B read, sigma 8 B written + 8 B read,
+    coef 8 B written = 26 B; per (source, shortest-path link): sigma gather 8 B + coef gather
+    8 B; per (batch, link): partial load written + read by the ordered reduction = 16 B.
+    Split by pass so that each kernel class can be priced on its own share.
+    """
+    pairs = src * N
+    nb = (src + 63) // 64
+    return {
+        "bfs": 1 * pairs,
+        "fwd": (1 + 8) * pairs + 8 * dag_links,
+        "bwd": (8 + 8) * pairs + 8 * dag_links + 8 * nb * E,
+        "reduce": 8 * nb * E,
+    }
+
+
+def read_traffic(kernel):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "c5_pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^%s\s+traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)" % re.escape(kernel),
+                  open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="C5")
+    ap.add_argument("--cpu-sources", type=int, default=None,
+                    help="sources in the oracle's timed sample (default: sized for ~10-20 s)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--max-workspace-gib", type=float, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (sources would shard across GPUs with one "
+              "ordered sum of E doubles at the end; see DESIGN.md). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import a2a_inputs as gen
+    import paper_2309_13541_amd as a2a
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    a2a.load_library()
+    torch.cuda.set_device(0)
+    rp, col = gen.named_config(args.config)
+    t0 = time.perf_counter()
+    topo = a2a.Topology(rp, col)
+    t_create = time.perf_counter() - t0
+    N, E = topo.N, topo.E
+    cap = None if args.max_workspace_gib is None else int(args.max_workspace_gib * 2 ** 30)
+    ws = topo.alloc_workspace(N, a2a.WS_LOADS, cap)
+    load = torch.empty(E, dtype=torch.float64, device="cuda")
+    dsum = torch.zeros(1, dtype=torch.int64, device="cuda")
+    flags = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+    def step():
+        topo.link_loads(0, N, load=load, dist_sum_total=dsum, flags=flags, workspace=ws)
+        # sum_dist / flags stay on the device until the end; the bound needs Lmax only
+        return topo.schedule_bound(load, 0, 0, 1.0, 1.0)[0]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    topo.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        bound = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = topo.profile_read()
+    topo.profile_enable(False)
+    sec = elapsed / args.steps
+    sum_dist = int(dsum.item())
+    fl = int(flags.item())
+    bound, _ = topo.schedule_bound(load, sum_dist, fl, 1.0, 1.0, allow_disconnected=True)
+
+    steps = args.steps
+    dag = prof["dag_links"] // max(prof["calls"], 1)
+    alg = algorithmic_bytes(N, E, N, dag)
+    per_class = {}
+    for k in ("bfs", "fwd", "bwd", "reduce"):
+        ms, n = prof[k]["ms"], prof[k]["launches"]
+        if n:
+            per_class[k] = {"ms_per_step": ms / steps, "launches_per_step": n // steps,
+                            "avg_launch_ms": ms / n,
+                            "alg_GBps": alg[k] / (ms / steps * 1e-3) / 1e9 if ms > 0 else None}
+    dom = max(("bfs", "fwd", "bwd", "reduce"), key=lambda k: prof[k]["ms"])
+    kname = {"bfs": "k_bfs_level", "fwd": "k_fwd_level", "bwd": "k_bwd_level", "reduce": "k_reduce_part"}[dom]
+    n_l = prof[dom]["launches"]
+    achieved = alg[dom] * steps / n_l / (prof[dom]["ms"] / n_l * 1e-3) / 1e9
+    alg_total = sum(alg.values())
+    roofline = {
+        "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kname),
+        "alg_bytes_per_launch": alg[dom] * steps / n_l, "avg_launch_ms": prof[dom]["ms"] / n_l,
+        "whole_path": {"alg_bytes": alg_total, "GBps": alg_total / sec / 1e9,
+                       "frac": alg_total / sec / 1e9 / HBM_PEAK_GBPS},
+        "per_class": per_class,
+    }
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        oracle.build(force=False)
+        cores = min(os.cpu_count() or 1, 16)
+        sample = args.cpu_sources
+        if sample is None:
+            # probe 4 sources per thread, then size the sample for about 12 s
+            p = min(N, 4 * cores)
+            tp = time.perf_counter(); oracle.run(rp, col, 0, p, threads=cores); tp = time.perf_counter() - tp
+            sample = int(max(p, min(N, p * 12.0 / max(tp, 1e-4))))
+        tc = time.perf_counter()
+        res = oracle.run(rp, col, 0, sample, threads=cores)
+        tc = time.perf_counter() - tc
+        cpu = {"value": sample * E / tc, "unit": "edges/s", "cores": res.threads, "kind": "oracle",
+               "sample": f"sources 0..{sample - 1} of {N} on the same CSR ({tc:.1f} s); "
+                         f"serial BFS + dependency pass per source, sources split over threads",
+               "seconds": tc}
+
+    out = {
+        "metric": "all_pairs_bfs_link_load_teps", "value": N * E / sec, "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: " + {
+            "C1": "8x8 torus", "C2": "hypercube n=10", "C3": "16x16x16 torus",
+            "C4": "Imase-Itoh N=16384 d=4", "C5": "random 8-regular digraph N=65536 seed 1234",
+        }[args.config] + ", unit all-pairs demand", "N": N, "E": E, "sources": N,
+            "workspace_GiB": ws.numel() / 2 ** 30, "groups_per_step": prof["groups"] // max(prof["calls"], 1),
+            "depth": prof["depth"], "dag_links": dag},
+        "result": {"sum_dist": sum_dist, "max_load": bound.max_load, "argmax_arc": bound.argmax_arc,
+                   "ratio_to_lower_bound": bound.ratio, "flags": fl},
+        "topo_create_ms": t_create * 1e3,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -7,6 +7,8 @@ package does not load the library; the first call does, and fails loudly if it i
 from .binding import (  # noqa: F401
     A2AError,
     Bound,
+    Profile,
+    PROF_CLASSES,
     Topology,
     build_library,
     library_path,

@@ -38,7 +38,10 @@ FLAG_UNREACHABLE = 0x2
 EXPORTED_SYMBOLS = (
     "a2a_topo_create", "a2a_topo_destroy", "a2a_topo_info", "a2a_workspace_bytes",
     "a2a_distances", "a2a_link_loads", "a2a_schedule_bound", "a2a_status_string",
+    "a2a_profile_enable", "a2a_profile_read",
 )
+
+PROF_CLASSES = ("init", "bfs", "fwd", "bwd", "reduce", "extract")
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -64,6 +67,20 @@ class Bound(ctypes.Structure):
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Profile(ctypes.Structure):
+    """Mirror of ``a2a_profile``."""
+    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int64 * 8),
+                ("dag_links", ctypes.c_int64), ("calls", ctypes.c_int64),
+                ("depth", ctypes.c_int32), ("groups", ctypes.c_int32)]
+
+    def as_dict(self) -> dict:
+        d = {"dag_links": self.dag_links, "calls": self.calls, "depth": self.depth,
+             "groups": self.groups}
+        for i, n in enumerate(PROF_CLASSES):
+            d[n] = {"ms": self.ms[i], "launches": self.launches[i]}
+        return d
 
 
 def library_path() -> str:
@@ -92,6 +109,10 @@ def load_library():
         raise RuntimeError(
             f"{_LIB} is missing: build it with paper_2309_13541_amd.build_library() "
             "(or __graft_entry__.build()); there is no CPU fallback")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  It has to be in the
+    # process first, so that this library binds to the runtime that owns torch's tensors and
+    # streams instead of bringing in a second one.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     lib.a2a_topo_create.restype = ctypes.c_int
@@ -110,6 +131,10 @@ def load_library():
     lib.a2a_schedule_bound.restype = ctypes.c_int
     lib.a2a_schedule_bound.argtypes = [vp, vp, i64, i64, ctypes.c_double, ctypes.c_double,
                                        ctypes.POINTER(Bound), vp]
+    lib.a2a_profile_enable.restype = ctypes.c_int
+    lib.a2a_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.a2a_profile_read.restype = ctypes.c_int
+    lib.a2a_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
     lib.a2a_status_string.restype = ctypes.c_char_p
     lib.a2a_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -184,6 +209,14 @@ class Topology:
             self._h, src_begin, src_count, _ptr(load), _ptr(dist_sum_total), _ptr(flags),
             _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream)),
             "a2a_link_loads")
+
+    def profile_enable(self, on: bool = True) -> None:
+        _check(load_library().a2a_profile_enable(self._h, 1 if on else 0), "a2a_profile_enable")
+
+    def profile_read(self) -> dict:
+        out = Profile()
+        _check(load_library().a2a_profile_read(self._h, ctypes.byref(out)), "a2a_profile_read")
+        return out.as_dict()
 
     def schedule_bound(self, load, sum_dist: int, flags: int = 0, m_bytes: float = 1.0,
                        b_bytes_per_s: float = 1.0, stream=None, allow_disconnected: bool = False):

@@ -30,7 +30,7 @@ constexpr int kXcd = 8;                        // workgroups are dealt round-rob
 constexpr double kTwo53 = 9007199254740992.0;
 
 // per-batch integer counters kept in the workspace control block
-enum { CNT_DSUM = 0, CNT_REACHED = 1, CNT_STRIDE = 2 };
+enum { CNT_DSUM = 0, CNT_REACHED = 1, CNT_DAG = 2, CNT_STRIDE = 4 };
 
 struct Layout {
   int G = 0;          // batches per group
@@ -38,7 +38,7 @@ struct Layout {
   int Npad = 0;       // N rounded up to a multiple of 64
   bool sigma = false, loads = false;
   size_t off_level_new = 0;  // int32 [Lcap]
-  size_t off_misc = 0;       // int64 [4]: 0 sigma-inexact flag, 1 dist_sum total, 2 reached total
+  size_t off_misc = 0;       // int64: 0 sigma-inexact flag, 1 dist_sum total, 2 reached total, 3 DAG links
   size_t off_cnt = 0;        // int64 [G][CNT_STRIDE]
   size_t off_lvl = 0;        // uint64 [G][Lcap][Npad]
   size_t off_seen = 0;       // uint64 [G][Npad]
@@ -62,7 +62,17 @@ struct a2a_topo {
   int32_t* d_in_ptr = nullptr;
   int32_t* d_in_col = nullptr;
   int64_t* h_pinned = nullptr;  // 16 x int64 pinned host words for read-backs
-  int64_t* d_small = nullptr;   // 16 x int64 device words (schedule_bound result)
+  int64_t* d_small = nullptr;   // 16 x int64 device words (schedule_bound result, profile counters)
+  // optional per-kernel timing (a2a_profile_enable); events are created per launch while it is on
+  struct ProfRec {
+    int cls;
+    hipEvent_t beg, end;
+  };
+  mutable bool prof_on = false;
+  mutable std::vector<ProfRec> prof_recs;
+  mutable int64_t prof_calls = 0;
+  mutable int32_t prof_depth = 0;
+  mutable int32_t prof_groups = 0;
 };
 
 namespace {
@@ -141,13 +151,14 @@ __device__ __forceinline__ long long wave_sum_i64(long long x) {
   return x;
 }
 
-// Workgroups go round-robin to the 8 XCDs, each with its own L2.  Give all workgroups of one
-// batch to one XCD, so that the rows its waves gather stay in that XCD's L2.
-__device__ __forceinline__ bool map_block(int G, int blocks_per_batch, int& g, int& nblk) {
+// Workgroups go round-robin to the 8 XCDs, each with its own L2.  `inflight` consecutive
+// workgroups belong to `inflight` different batches; with inflight = 8 all workgroups of one
+// batch run on one XCD, so that the rows its waves gather stay in that XCD's L2.
+__device__ __forceinline__ bool map_block(int G, int blocks_per_batch, int inflight, int& g, int& nblk) {
   const unsigned blk = blockIdx.x;
-  const unsigned x = blk % kXcd;
-  const unsigned i = blk / kXcd;
-  g = (int)((i / (unsigned)blocks_per_batch) * kXcd + x);
+  const unsigned x = blk % (unsigned)inflight;
+  const unsigned i = blk / (unsigned)inflight;
+  g = (int)((i / (unsigned)blocks_per_batch) * inflight + x);
   nblk = (int)(i % (unsigned)blocks_per_batch);
   return g < G;
 }
@@ -166,7 +177,7 @@ __global__ void __launch_bounds__(kBlock)
 k_init_group(uint64_t* __restrict__ lvl, uint64_t* __restrict__ seen, double* __restrict__ sig,
              int N, int Npad, int Lcap, int G, int bpb, int src_begin, int src_count, int batch0) {
   int g, nblk;
-  if (!map_block(G, bpb, g, nblk)) return;
+  if (!map_block(G, bpb, kXcd, g, nblk)) return;
   const int v = nblk * kBlock + (int)threadIdx.x;
   if (v >= Npad) return;
   const int s0 = src_begin + (batch0 + g) * 64;
@@ -186,7 +197,7 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
             int G, int bpb, int level, int src_count, int batch0, int* __restrict__ level_new,
             long long* __restrict__ cnt) {
   int g, nblk;
-  if (!map_block(G, bpb, g, nblk)) return;
+  if (!map_block(G, bpb, kXcd, g, nblk)) return;
   const int v = nblk * kBlock + (int)threadIdx.x;
   uint64_t nw = 0;
   if (v < Npad) {
@@ -223,14 +234,67 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   }
 }
 
+// Lane exchange with lane ^ kMask, for the 64-bit reductions below.
+template <int kMask>
+__device__ __forceinline__ double xor_lanes(double x) {
+  union {
+    double d;
+    int i[2];
+  } a, b;
+  a.d = x;
+  if constexpr (kMask == 1) {  // DPP quad_perm [1,0,3,2]
+    b.i[0] = __builtin_amdgcn_mov_dpp(a.i[0], 0xB1, 0xF, 0xF, true);
+    b.i[1] = __builtin_amdgcn_mov_dpp(a.i[1], 0xB1, 0xF, 0xF, true);
+  } else if constexpr (kMask == 2) {  // DPP quad_perm [2,3,0,1]
+    b.i[0] = __builtin_amdgcn_mov_dpp(a.i[0], 0x4E, 0xF, 0xF, true);
+    b.i[1] = __builtin_amdgcn_mov_dpp(a.i[1], 0x4E, 0xF, 0xF, true);
+  } else if constexpr (kMask < 32) {  // ds_swizzle, bit mode: and 0x1f, or 0, xor kMask
+    b.i[0] = __builtin_amdgcn_ds_swizzle(a.i[0], 0x1F | (kMask << 10));
+    b.i[1] = __builtin_amdgcn_ds_swizzle(a.i[1], 0x1F | (kMask << 10));
+  } else {
+    return __shfl_xor(x, kMask, kWave);
+  }
+  return b.d;
+}
+
+// Eight 64-lane sums at once.  x[i] is lane-local; on return every lane l holds the sum over
+// all 64 lanes of x[l & 7].  Halving the value set at each of the first three exchange steps
+// costs 4+2+1+3 exchanges instead of 8*6, in a fixed order.
+__device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+  double y[4], z[2];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const double keep = b0 ? x[2 * k + 1] : x[2 * k];
+    const double send = b0 ? x[2 * k] : x[2 * k + 1];
+    y[k] = keep + xor_lanes<1>(send);
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const double keep = b1 ? y[2 * k + 1] : y[2 * k];
+    const double send = b1 ? y[2 * k] : y[2 * k + 1];
+    z[k] = keep + xor_lanes<2>(send);
+  }
+  const double keep = b2 ? z[1] : z[0];
+  const double send = b2 ? z[0] : z[1];
+  double w = keep + xor_lanes<4>(send);
+  w += xor_lanes<8>(w);
+  w += xor_lanes<16>(w);
+  w += xor_lanes<32>(w);
+  return w;
+}
+
 // Forward path counts for one level: each wave takes 64 consecutive nodes of one batch and
-// visits those with a non-empty L_level mask.  Lane j = source j.
+// visits those with a non-empty L_level mask.  Lane j = source j.  In-links are taken eight at
+// a time so that eight row gathers are in flight per wave.
+template <bool kCountDag>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col,
             const uint64_t* __restrict__ lvl, double* __restrict__ sig, int N, int Npad, int Lcap,
-            int G, int bpb, int level, long long* __restrict__ misc) {
+            int G, int bpb, int inflight, int level, long long* __restrict__ misc,
+            long long* __restrict__ cnt) {
   int g, nblk;
-  if (!map_block(G, bpb, g, nblk)) return;
+  if (!map_block(G, bpb, inflight, g, nblk)) return;
   const int lane = lane_id();
   const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (v0 >= N) return;
@@ -240,6 +304,7 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   const uint64_t my_new = cur[v0 + lane];  // Npad is a multiple of 64: in bounds, 0 beyond N
   uint64_t todo = __ballot(my_new != 0);
   bool inexact = false;
+  long long dag = 0;  // (source, link) pairs on shortest paths seen by this wave
   while (todo) {
     const int k = __builtin_ctzll(todo);
     todo &= todo - 1;
@@ -253,11 +318,18 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
       const uint64_t m_l = q < p1 ? (prev[u_l] & newv) : 0ull;
       uint64_t act = __ballot(m_l != 0);
       while (act) {
-        const int j = __builtin_ctzll(act);
-        act &= act - 1;
-        const int u = __builtin_amdgcn_readlane(u_l, j);
-        const uint64_t m = readlane64(m_l, j);
-        if ((m >> lane) & 1ull) acc += sg[(size_t)u * 64 + lane];
+        const int c = __builtin_ctzll(act) & ~7;  // first lane position of the next octet of links
+        act &= ~(0xffull << c);
+        double x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int u = __builtin_amdgcn_readlane(u_l, c + i);
+          const uint64_t m = readlane64(m_l, c + i);
+          if (kCountDag) dag += __popcll(m);
+          x[i] = ((m >> lane) & 1ull) ? sg[(size_t)u * 64 + lane] : 0.0;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc += x[i];
       }
     }
     if ((newv >> lane) & 1ull) {
@@ -266,17 +338,20 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     }
   }
   if (inexact) misc[0] = 1;
+  if (kCountDag && dag != 0 && lane == 0)
+    atomicAdd((unsigned long long*)&cnt[g * CNT_STRIDE + CNT_DAG], (unsigned long long)dag);
 }
 
 // Backward dependency pass for one level.  On entry sig holds sigma for levels <= level and
 // coef for deeper levels; on exit the nodes of this level hold coef.  part[a] accumulates the
-// batch's load of link a.
+// batch's load of link a.  Out-links are taken eight at a time: eight row gathers in flight,
+// then one eight-way wave reduction of sigma[u]*coef[w] per link.
 __global__ void __launch_bounds__(kBlock)
 k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col,
             const uint64_t* __restrict__ lvl, double* __restrict__ sig, double* __restrict__ part,
-            size_t Epad, int N, int Npad, int Lcap, int G, int bpb, int level) {
+            size_t Epad, int N, int Npad, int Lcap, int G, int bpb, int inflight, int level) {
   int g, nblk;
-  if (!map_block(G, bpb, g, nblk)) return;
+  if (!map_block(G, bpb, inflight, g, nblk)) return;
   const int lane = lane_id();
   const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (u0 >= N) return;
@@ -300,19 +375,24 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
       const int w_l = q < p1 ? out_col[q] : 0;
       const uint64_t m_l = q < p1 ? (next[w_l] & mu) : 0ull;
       uint64_t act = __ballot(m_l != 0);
-      double x_l = 0.0;  // lane j ends up with the load of link p + j
-      const bool any = act != 0;
       while (act) {
-        const int j = __builtin_ctzll(act);
-        act &= act - 1;
-        const int w = __builtin_amdgcn_readlane(w_l, j);
-        const uint64_t m = readlane64(m_l, j);
-        const double c = ((m >> lane) & 1ull) ? sg[(size_t)w * 64 + lane] : 0.0;
-        acc += c;
-        const double x = wave_sum(s_u * c);
-        if (lane == j) x_l = x;
+        const int c = __builtin_ctzll(act) & ~7;
+        act &= ~(0xffull << c);
+        double x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int w = __builtin_amdgcn_readlane(w_l, c + i);
+          const uint64_t m = readlane64(m_l, c + i);
+          x[i] = ((m >> lane) & 1ull) ? sg[(size_t)w * 64 + lane] : 0.0;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          acc += x[i];
+          x[i] *= s_u;
+        }
+        const double tot = wave_sum8(x, lane);  // lane l: load of link p + c + (l & 7)
+        if ((lane & ~7) == c && m_l != 0) pt[q] += tot;
       }
-      if (any && m_l != 0) pt[q] += x_l;
     }
     if (mine) sg[(size_t)u * 64 + lane] = 1.0 / s_u + acc;
   }
@@ -336,7 +416,7 @@ k_extract_dist(const uint64_t* __restrict__ lvl, int N, int Npad, int Lcap, int 
                int depth, int src_count, int batch0, int32_t* __restrict__ dist,
                long long* __restrict__ dist_sum) {
   int g, tile;
-  if (!map_block(G, tiles, g, tile)) return;
+  if (!map_block(G, tiles, kXcd, g, tile)) return;
   __shared__ int32_t t_d[kWave][kWave + 1];
   const int t = (int)threadIdx.x;
   const int v = tile * kWave + t;
@@ -371,7 +451,7 @@ __global__ void __launch_bounds__(kWave)
 k_extract_sigma(const uint64_t* __restrict__ seen, const double* __restrict__ sig, int N, int Npad,
                 int G, int tiles, int src_count, int batch0, double* __restrict__ sigma_out) {
   int g, tile;
-  if (!map_block(G, tiles, g, tile)) return;
+  if (!map_block(G, tiles, kXcd, g, tile)) return;
   __shared__ double t_s[kWave][kWave + 1];
   const int t = (int)threadIdx.x;
   const int v0 = tile * kWave;
@@ -393,22 +473,25 @@ k_extract_sigma(const uint64_t* __restrict__ seen, const double* __restrict__ si
 // Folds the per-batch counters of a group into the running totals.
 __global__ void k_fold_counters(const long long* __restrict__ cnt, int G, long long* __restrict__ misc) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
-    long long ds = 0, rc = 0;
+    long long ds = 0, rc = 0, dg = 0;
     for (int g = 0; g < G; ++g) {
       ds += cnt[g * CNT_STRIDE + CNT_DSUM];
       rc += cnt[g * CNT_STRIDE + CNT_REACHED];
+      dg += cnt[g * CNT_STRIDE + CNT_DAG];
     }
     misc[1] += ds;
     misc[2] += rc;
+    misc[3] += dg;
   }
 }
 
 // Final outputs of a call: totals and flag bits.
 __global__ void k_finish(const long long* __restrict__ misc, long long pairs,
                          long long* __restrict__ dist_sum_total, long long* __restrict__ unreachable,
-                         long long* __restrict__ flags) {
+                         long long* __restrict__ flags, long long* __restrict__ prof_out) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     const long long unr = pairs - misc[2];
+    if (prof_out) prof_out[8] += misc[3];
     if (dist_sum_total) *dist_sum_total = misc[1];
     if (unreachable) *unreachable = unr;
     if (flags) *flags = (misc[0] ? A2A_FLAG_SIGMA_INEXACT : 0) | (unr ? A2A_FLAG_UNREACHABLE : 0);
@@ -466,8 +549,39 @@ k_load_extrema(const double* __restrict__ load, long long E, long long* __restri
     }                                     \
   } while (0)
 
-inline int grid_for(int G, int blocks_per_batch) {
-  return (G + kXcd - 1) / kXcd * kXcd * blocks_per_batch;
+// Brackets one kernel launch with two events while profiling is on.
+struct ProfScope {
+  const a2a_topo* t;
+  hipStream_t st;
+  a2a_topo::ProfRec rec{};
+  bool live = false;
+  ProfScope(const a2a_topo* t_, int cls, hipStream_t st_) : t(t_), st(st_) {
+    if (!t->prof_on) return;
+    rec.cls = cls;
+    if (hipEventCreate(&rec.beg) != hipSuccess) return;
+    if (hipEventCreate(&rec.end) != hipSuccess) {
+      (void)hipEventDestroy(rec.beg);
+      return;
+    }
+    live = hipEventRecord(rec.beg, st) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!live) return;
+    (void)hipEventRecord(rec.end, st);
+    t->prof_recs.push_back(rec);
+  }
+};
+
+enum { PROF_INIT = 0, PROF_BFS, PROF_FWD, PROF_BWD, PROF_REDUCE, PROF_EXTRACT, PROF_CLASSES };
+
+inline int grid_for(int G, int blocks_per_batch, int inflight = kXcd) {
+  return (G + inflight - 1) / inflight * inflight * blocks_per_batch;
+}
+
+inline int env_inflight() {
+  const char* e = std::getenv("A2A_INFLIGHT");
+  const int v = e ? std::atoi(e) : kXcd;
+  return v >= 1 && v <= 64 ? v : kXcd;
 }
 
 // Eccentricity of node 0 over the given CSR by queue BFS; -1 if some node is not reached.
@@ -496,6 +610,7 @@ struct Run {
   char* ws;
   hipStream_t st;
   int src_begin, src_count;
+  int inflight = env_inflight();
   int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
   long long* cnt() const { return (long long*)(ws + L.off_cnt); }
@@ -512,14 +627,20 @@ int run_bfs(const Run& r, int batch0, int G, int* depth) {
   const int bpb = (L.Npad + kBlock - 1) / kBlock;
   HIP_TRY(hipMemsetAsync(r.level_new(), 0, (size_t)L.Lcap * 4, r.st));
   HIP_TRY(hipMemsetAsync(r.cnt(), 0, (size_t)G * CNT_STRIDE * 8, r.st));
-  k_init_group<<<grid_for(G, bpb), kBlock, 0, r.st>>>(r.lvl(), r.seen(), r.sig(), t->N, L.Npad, L.Lcap,
-                                                      G, bpb, r.src_begin, r.src_count, batch0);
+  {
+    ProfScope ps(t, PROF_INIT, r.st);
+    k_init_group<<<grid_for(G, bpb), kBlock, 0, r.st>>>(r.lvl(), r.seen(), r.sig(), t->N, L.Npad, L.Lcap,
+                                                        G, bpb, r.src_begin, r.src_count, batch0);
+  }
   int d = 0;
   int l = 1;
   for (; l < L.Lcap; ++l) {
-    k_bfs_level<<<grid_for(G, bpb), kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, r.lvl(), r.seen(), t->N,
-                                                       L.Npad, L.Lcap, G, bpb, l, r.src_count, batch0,
-                                                       r.level_new(), r.cnt());
+    {
+      ProfScope ps(t, PROF_BFS, r.st);
+      k_bfs_level<<<grid_for(G, bpb), kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, r.lvl(), r.seen(), t->N,
+                                                         L.Npad, L.Lcap, G, bpb, l, r.src_count, batch0,
+                                                         r.level_new(), r.cnt());
+    }
     HIP_TRY(hipMemcpyAsync(t->h_pinned, r.level_new() + l, 4, hipMemcpyDeviceToHost, r.st));
     HIP_TRY(hipStreamSynchronize(r.st));
     if (*(volatile int*)t->h_pinned == 0) break;
@@ -527,8 +648,9 @@ int run_bfs(const Run& r, int batch0, int G, int* depth) {
   }
   if (l == L.Lcap) return A2A_ERR_LEVEL_OVERFLOW;
   HIP_TRY(hipGetLastError());
-  k_fold_counters<<<1, 64, 0, r.st>>>(r.cnt(), G, r.misc());
   *depth = d;
+  if (d > t->prof_depth) t->prof_depth = d;
+  t->prof_groups++;
   return A2A_OK;
 }
 
@@ -536,9 +658,24 @@ int run_fwd(const Run& r, int G, int depth) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
   const int bpb = (L.Npad + kBlock - 1) / kBlock;
-  for (int l = 1; l <= depth; ++l)
-    k_fwd_level<<<grid_for(G, bpb), kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, r.lvl(), r.sig(), t->N,
-                                                       L.Npad, L.Lcap, G, bpb, l, r.misc());
+  for (int l = 1; l <= depth; ++l) {
+    ProfScope ps(t, PROF_FWD, r.st);
+    if (t->prof_on)
+      k_fwd_level<true><<<grid_for(G, bpb, r.inflight), kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, r.lvl(), r.sig(),
+                                                               t->N, L.Npad, L.Lcap, G, bpb, r.inflight, l, r.misc(),
+                                                               r.cnt());
+    else
+      k_fwd_level<false><<<grid_for(G, bpb, r.inflight), kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, r.lvl(), r.sig(),
+                                                                t->N, L.Npad, L.Lcap, G, bpb, r.inflight, l, r.misc(),
+                                                                r.cnt());
+  }
+  HIP_TRY(hipGetLastError());
+  return A2A_OK;
+}
+
+// Per-batch counters of the finished group go into the call's running totals.
+int run_fold(const Run& r, int G) {
+  k_fold_counters<<<1, 64, 0, r.st>>>(r.cnt(), G, r.misc());
   HIP_TRY(hipGetLastError());
   return A2A_OK;
 }
@@ -687,16 +824,21 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
     if (sigma) {
       rc = run_fwd(r, G, depth);
       if (rc != A2A_OK) return rc;
+      ProfScope ps(t, PROF_EXTRACT, st);
       k_extract_sigma<<<grid_for(G, tiles), kWave, 0, st>>>(r.seen(), r.sig(), t->N, L.Npad, G, tiles,
                                                            src_count, b0, sigma);
     }
-    if (dist || dist_sum)
+    if (dist || dist_sum) {
+      ProfScope ps(t, PROF_EXTRACT, st);
       k_extract_dist<<<grid_for(G, tiles), kWave, 0, st>>>(r.lvl(), t->N, L.Npad, L.Lcap, G, tiles, depth,
                                                           src_count, b0, dist, (long long*)dist_sum);
-    HIP_TRY(hipGetLastError());
+    }
+    rc = run_fold(r, G);
+    if (rc != A2A_OK) return rc;
   }
   k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), nullptr, (long long*)unreachable,
-                             (long long*)flags);
+                             (long long*)flags, t->prof_on ? (long long*)t->d_small : nullptr);
+  t->prof_calls++;
   HIP_TRY(hipGetLastError());
   return A2A_OK;
 }
@@ -735,17 +877,22 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (rc != A2A_OK) return rc;
     if (t->E > 0) {
       HIP_TRY(hipMemsetAsync(r.part(), 0, (size_t)G * L.Epad * 8, st));
-      for (int l = depth; l >= 0; --l)
-        k_bwd_level<<<grid_for(G, bpb), kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, r.lvl(), r.sig(),
-                                                         r.part(), L.Epad, t->N, L.Npad, L.Lcap, G, bpb, l);
+      for (int l = depth; l >= 0; --l) {
+        ProfScope ps(t, PROF_BWD, st);
+        k_bwd_level<<<grid_for(G, bpb, r.inflight), kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, r.lvl(), r.sig(),
+                                                         r.part(), L.Epad, t->N, L.Npad, L.Lcap, G, bpb, r.inflight, l);
+      }
+      ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(r.part(), L.Epad, G,
                                                                                  (long long)t->E,
                                                                                  b0 == 0 ? 1 : 0, load);
     }
-    HIP_TRY(hipGetLastError());
+    rc = run_fold(r, G);
+    if (rc != A2A_OK) return rc;
   }
   k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), (long long*)dist_sum_total,
-                             nullptr, (long long*)flags);
+                             nullptr, (long long*)flags, t->prof_on ? (long long*)t->d_small : nullptr);
+  t->prof_calls++;
   HIP_TRY(hipGetLastError());
   return A2A_OK;
 }
@@ -778,6 +925,41 @@ int a2a_schedule_bound(const a2a_topo* t, const double* load, int64_t sum_dist, 
   out->flow_value = 1.0 / lmax;
   out->throughput_upper = (double)(t->N - 1) * out->flow_value * b;
   return (flags & A2A_FLAG_UNREACHABLE) ? A2A_ERR_DISCONNECTED : A2A_OK;
+}
+
+int a2a_profile_enable(a2a_topo* t, int on) {
+  if (!t) return A2A_ERR_INVALID_ARG;
+  for (auto& rec : t->prof_recs) {
+    (void)hipEventDestroy(rec.beg);
+    (void)hipEventDestroy(rec.end);
+  }
+  t->prof_recs.clear();
+  t->prof_calls = 0;
+  t->prof_depth = 0;
+  t->prof_groups = 0;
+  t->prof_on = on != 0;
+  HIP_TRY(hipMemset(t->d_small + 8, 0, 8 * sizeof(int64_t)));
+  return A2A_OK;
+}
+
+int a2a_profile_read(a2a_topo* t, a2a_profile* out) {
+  if (!t || !out) return A2A_ERR_INVALID_ARG;
+  std::memset(out, 0, sizeof(*out));
+  HIP_TRY(hipDeviceSynchronize());
+  for (auto& rec : t->prof_recs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, rec.beg, rec.end) == hipSuccess && rec.cls >= 0 && rec.cls < PROF_CLASSES) {
+      out->ms[rec.cls] += ms;
+      out->launches[rec.cls] += 1;
+    }
+  }
+  int64_t dag = 0;
+  HIP_TRY(hipMemcpy(&dag, t->d_small + 8, sizeof(dag), hipMemcpyDeviceToHost));
+  out->dag_links = dag;
+  out->calls = t->prof_calls;
+  out->depth = t->prof_depth;
+  out->groups = t->prof_groups;
+  return A2A_OK;
 }
 
 }  // extern "C"
