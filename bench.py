@@ -90,24 +90,28 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    topo.profile_enable(True)
+    topo.profile_enable(1)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         bound = step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = topo.profile_read()
-    topo.profile_enable(False)
+    # one more, untimed, step counts the (source, link) pairs on shortest paths
+    topo.profile_enable(2)
+    step()
+    dag = topo.profile_read()["dag_links"]
+    topo.profile_enable(0)
     sec = elapsed / args.steps
     sum_dist = int(dsum.item())
     fl = int(flags.item())
     bound, _ = topo.schedule_bound(load, sum_dist, fl, 1.0, 1.0, allow_disconnected=True)
 
     steps = args.steps
-    dag = prof["dag_links"] // max(prof["calls"], 1)
     alg = algorithmic_bytes(N, E, N, dag)
     per_class = {}
-    for k in ("bfs", "fwd", "bwd", "reduce"):
+    alg["offsets"] = 0
+    for k in ("bfs", "offsets", "fwd", "bwd", "reduce"):
         ms, n = prof[k]["ms"], prof[k]["launches"]
         if n:
             per_class[k] = {"ms_per_step": ms / steps, "launches_per_step": n // steps,
@@ -118,6 +122,7 @@ def main():
     n_l = prof[dom]["launches"]
     achieved = alg[dom] * steps / n_l / (prof[dom]["ms"] / n_l * 1e-3) / 1e9
     alg_total = sum(alg.values())
+    timed_calls = max(prof["calls"], 1)
     roofline = {
         "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kname),
@@ -155,7 +160,7 @@ def main():
             "C1": "8x8 torus", "C2": "hypercube n=10", "C3": "16x16x16 torus",
             "C4": "Imase-Itoh N=16384 d=4", "C5": "random 8-regular digraph N=65536 seed 1234",
         }[args.config] + ", unit all-pairs demand", "N": N, "E": E, "sources": N,
-            "workspace_GiB": ws.numel() / 2 ** 30, "groups_per_step": prof["groups"] // max(prof["calls"], 1),
+            "workspace_GiB": ws.numel() / 2 ** 30, "groups_per_step": prof["groups"] // timed_calls,
             "depth": prof["depth"], "dag_links": dag},
         "result": {"sum_dist": sum_dist, "max_load": bound.max_load, "argmax_arc": bound.argmax_arc,
                    "ratio_to_lower_bound": bound.ratio, "flags": fl},

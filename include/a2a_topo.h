@@ -111,7 +111,7 @@ int a2a_distances(const a2a_topo* topo, int32_t src_begin, int32_t src_count, in
  *   load[a] = sum_s sum_{t != s} (# shortest s->t paths through link a) / sigma(s,t).
  * Computed per source batch by a forward path-count pass and a backward dependency pass over
  * the shortest-path DAG; batch results are added in ascending batch order, so the result is
- * bitwise reproducible for a given workspace size.
+ * bitwise reproducible whatever the workspace size.
  *   load            device, double[E], overwritten
  *   dist_sum_total  device, int64[1]: sum over these sources of sum_t D(s,t).  May be NULL.
  *   flags           device, int64[1]: A2A_FLAG_* bits.  May be NULL.
@@ -152,24 +152,27 @@ int a2a_schedule_bound(const a2a_topo* topo, const double* load, int64_t sum_dis
                        double m_bytes, double b_bytes_per_s, a2a_bound* out, void* hip_stream);
 
 /*
- * Optional per-kernel timing, for benchmarks (not part of the paper's method).  While enabled,
- * every launch of a2a_distances / a2a_link_loads on this handle is bracketed by two HIP events
- * on the caller's stream, and the forward pass also counts the (source, link) pairs that lie on
- * shortest paths.  a2a_profile_enable(topo, 0 or 1) clears what was gathered so far.
+ * Optional per-kernel timing, for benchmarks (not part of the paper's method).
+ * a2a_profile_enable(topo, mode) clears what was gathered so far and sets the mode:
+ *   0  off (default);
+ *   1  every kernel launch of a2a_distances / a2a_link_loads on this handle is bracketed by two
+ *      HIP events on the caller's stream (a few microseconds per launch);
+ *   2  as 1, and the forward pass also counts the (source, link) pairs that lie on shortest
+ *      paths (one atomic per wavefront: slows the forward kernels down, use on untimed runs).
  * a2a_profile_read waits for the device and sums the event times per kernel class; index
- * A2A_PROF_* into ms[] / launches[].  Not thread safe; costs a few microseconds per launch.
+ * A2A_PROF_* into ms[] / launches[].  Not thread safe.
  */
 enum { A2A_PROF_INIT = 0, A2A_PROF_BFS, A2A_PROF_FWD, A2A_PROF_BWD, A2A_PROF_REDUCE, A2A_PROF_EXTRACT,
-       A2A_PROF_CLASSES };
+       A2A_PROF_OFFSETS, A2A_PROF_CLASSES };
 typedef struct a2a_profile {
   double ms[8];        /* summed kernel time per class, milliseconds */
   int64_t launches[8]; /* launches per class */
-  int64_t dag_links;   /* sum over sources of links (u,w) with D(s,w) = D(s,u) + 1 */
+  int64_t dag_links;   /* mode 2: sum over sources of links (u,w) with D(s,w) = D(s,u) + 1 */
   int64_t calls;       /* a2a_distances + a2a_link_loads calls since enable */
   int32_t depth;       /* deepest BFS level seen */
   int32_t groups;      /* batch groups processed */
 } a2a_profile;
-int a2a_profile_enable(a2a_topo* topo, int on);
+int a2a_profile_enable(a2a_topo* topo, int mode);
 int a2a_profile_read(a2a_topo* topo, a2a_profile* out);
 
 /* Static string for a status code. */

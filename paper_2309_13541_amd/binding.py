@@ -41,7 +41,7 @@ EXPORTED_SYMBOLS = (
     "a2a_profile_enable", "a2a_profile_read",
 )
 
-PROF_CLASSES = ("init", "bfs", "fwd", "bwd", "reduce", "extract")
+PROF_CLASSES = ("init", "bfs", "fwd", "bwd", "reduce", "extract", "offsets")
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -210,8 +210,9 @@ class Topology:
             _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream)),
             "a2a_link_loads")
 
-    def profile_enable(self, on: bool = True) -> None:
-        _check(load_library().a2a_profile_enable(self._h, 1 if on else 0), "a2a_profile_enable")
+    def profile_enable(self, mode: int = 1) -> None:
+        """0 off, 1 per-launch events, 2 events + count of shortest-path (source, link) pairs."""
+        _check(load_library().a2a_profile_enable(self._h, int(mode)), "a2a_profile_enable")
 
     def profile_read(self) -> dict:
         out = Profile()

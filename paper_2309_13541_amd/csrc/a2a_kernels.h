@@ -1,0 +1,665 @@
+// Device code of a2a_topo (gfx950, wave64).  Included once, by a2a_topo.hip.
+//
+// Data model.  Sources are handled 64 at a time ("batch"): bit j of a 64-bit mask = source j of
+// the batch, and lane j of a wavefront carries that source's floating-point state.  For every
+// batch and BFS level l the index array holds, per node v, the mask L_l[v] of sources that
+// reach v in exactly l hops (D(s,v) = l, the hop distance of Sec. 5.4) and an offset into the
+// batch's value array.  The value array is level-compact: the entries of (l, v) are the
+// popcount(L_l[v]) sources of that mask in lane order, rows follow each other in node order,
+// levels follow each other.  Every reachable (source, node) pair owns exactly one entry: it
+// holds sigma(s,v) (number of shortest paths, Sec. 5.2) after the forward pass and
+// coef(s,v) = (1 + delta(s,v)) / sigma(s,v) after the backward pass, where delta is the traffic
+// forwarded through v under the equal split of Sec. 5.2.  A link (u,w) is used by the sources
+// in L_l[u] & L_{l+1}[w]; a gather of row (l,u) therefore reads popcount(L_l[u]) values instead
+// of a 64-wide row, and a node's row is written once per pass instead of once per level.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace a2a_dev {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;  // threads per workgroup = nodes per node block
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kXcd = 8;      // workgroups are dealt round-robin to 8 XCDs
+constexpr double kTwo53 = 9007199254740992.0;
+// Up to this many (source, link) pairs per node the backward kernel adds the products lane by
+// lane; beyond it the eight-way wave reduction is cheaper.
+constexpr int kSerialPairs = 16;
+
+// One node of one (batch, level): 16 bytes so that mask and offset arrive in one request.
+struct __align__(16) NodeIdx {
+  uint64_t mask;  // L_level[v]
+  uint32_t off;   // first entry of the row in the batch's value array
+  uint32_t pad;
+};
+
+// ---------------------------------------------------------------------------------------
+// lane helpers
+// ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+__device__ __forceinline__ uint64_t readlane64(uint64_t x, int k) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, k);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), k);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t shfl64(uint64_t x, int src_lane) {
+  const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)x, src_lane, kWave);
+  const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)(x >> 32), src_lane, kWave);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Number of set bits of m below this lane: the rank of the lane's entry in a compact row.
+__device__ __forceinline__ uint32_t rank_in(uint64_t m) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// True in exactly the lanes whose bit is set in the wave-uniform mask m.  Lowers to a copy of
+// m into the execution mask: no per-lane compare.
+__device__ __forceinline__ bool lane_in(uint64_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+
+// Entry `e` of a batch's value array.  The 32-bit byte offset keeps the address computation to
+// one instruction (uniform base + per-lane offset); a batch's array is Npad*64*8 bytes, which
+// the host keeps below 4 GiB.
+__device__ __forceinline__ double& entry(double* __restrict__ dat, uint32_t e) {
+  return *reinterpret_cast<double*>(reinterpret_cast<char*>(dat) + (size_t)(e * 8u));
+}
+
+// 1/x for x >= 1: hardware estimate plus two Newton steps (relative error about 1e-16).
+__device__ __forceinline__ double recip(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+  r = __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+  return r;
+}
+
+__device__ __forceinline__ NodeIdx load_idx(const NodeIdx* __restrict__ p) {
+  const ulonglong2 r = *reinterpret_cast<const ulonglong2*>(p);
+  NodeIdx n;
+  n.mask = r.x;
+  n.off = (uint32_t)r.y;
+  n.pad = 0;
+  return n;
+}
+
+// Lane exchange with lane ^ kMask for a 64-bit value.
+template <int kMask>
+__device__ __forceinline__ double xor_lanes(double x) {
+  union {
+    double d;
+    int i[2];
+  } a, b;
+  a.d = x;
+  if constexpr (kMask == 1) {  // DPP quad_perm [1,0,3,2]
+    b.i[0] = __builtin_amdgcn_mov_dpp(a.i[0], 0xB1, 0xF, 0xF, true);
+    b.i[1] = __builtin_amdgcn_mov_dpp(a.i[1], 0xB1, 0xF, 0xF, true);
+  } else if constexpr (kMask == 2) {  // DPP quad_perm [2,3,0,1]
+    b.i[0] = __builtin_amdgcn_mov_dpp(a.i[0], 0x4E, 0xF, 0xF, true);
+    b.i[1] = __builtin_amdgcn_mov_dpp(a.i[1], 0x4E, 0xF, 0xF, true);
+  } else if constexpr (kMask < 32) {  // ds_swizzle, bit mode: and 0x1f, or 0, xor kMask
+    b.i[0] = __builtin_amdgcn_ds_swizzle(a.i[0], 0x1F | (kMask << 10));
+    b.i[1] = __builtin_amdgcn_ds_swizzle(a.i[1], 0x1F | (kMask << 10));
+  } else {
+    return __shfl_xor(x, kMask, kWave);
+  }
+  return b.d;
+}
+
+// Eight 64-lane sums at once.  x[i] is lane-local; on return every lane l holds the sum over
+// all 64 lanes of x[l & 7].  Halving the value set at each of the first three exchange steps
+// costs 4+2+1+3 exchanges instead of 8*6, in a fixed order (so results are reproducible).
+__device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+  double y[4], z[2];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const double keep = b0 ? x[2 * k + 1] : x[2 * k];
+    const double send = b0 ? x[2 * k] : x[2 * k + 1];
+    y[k] = keep + xor_lanes<1>(send);
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const double keep = b1 ? y[2 * k + 1] : y[2 * k];
+    const double send = b1 ? y[2 * k] : y[2 * k + 1];
+    z[k] = keep + xor_lanes<2>(send);
+  }
+  const double keep = b2 ? z[1] : z[0];
+  const double send = b2 ? z[0] : z[1];
+  double w = keep + xor_lanes<4>(send);
+  w += xor_lanes<8>(w);
+  w += xor_lanes<16>(w);
+  w += xor_lanes<32>(w);
+  return w;
+}
+
+__device__ __forceinline__ int wave_sum_int(int x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+  return x;
+}
+
+// Inclusive prefix sum over the lanes of a wave.
+__device__ __forceinline__ int wave_scan_incl(int x, int lane) {
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int y = __shfl_up(x, o, kWave);
+    if (lane >= o) x += y;
+  }
+  return x;
+}
+
+// Workgroups go round-robin to the 8 XCDs, each with its own L2.  `inflight` consecutive
+// workgroups belong to `inflight` different batches; with inflight = 8 all workgroups of one
+// batch run on one XCD, so that the small per-level arrays of that batch (masks, offsets, the
+// rows of sparsely populated levels) stay in that XCD's L2 while its waves gather from them.
+__device__ __forceinline__ bool map_block(int G, int blocks_per_batch, int inflight, int& g, int& nblk) {
+  const unsigned blk = blockIdx.x;
+  const unsigned x = blk % (unsigned)inflight;
+  const unsigned i = blk / (unsigned)inflight;
+  g = (int)((i / (unsigned)blocks_per_batch) * inflight + x);
+  nblk = (int)(i % (unsigned)blocks_per_batch);
+  return g < G;
+}
+
+__device__ __forceinline__ uint64_t valid_mask(int src_count, int batch) {
+  const int cnt = src_count - batch * 64;
+  return cnt >= 64 ? ~0ull : ((1ull << cnt) - 1ull);
+}
+
+// Everything a level kernel needs to find its batch's arrays.
+struct GroupView {
+  NodeIdx* idx;       // [G][Lcap][Npad]
+  uint64_t* seen;     // [G][Npad]
+  double* dat;        // [G][Npad*64]  level-compact values (nullptr: distances only)
+  int* bsum;          // [G][Lcap][bpb] newly reached pairs per node block and level
+  long long* ltot;    // [G][Lcap]      newly reached pairs per level
+  long long* dag;     // [G]            (source, link) pairs on shortest paths (profiling)
+  double* part;       // [G][Epad]      per-batch link loads
+  size_t Epad;
+  int N, Npad, Lcap, G, bpb, inflight;
+  int src_begin, src_count, batch0;
+};
+
+// ---------------------------------------------------------------------------------------
+// BFS
+// ---------------------------------------------------------------------------------------
+
+// Level 0: bit j of L_0[s_j] and seen[s_j] for the batch's sources s_j; sigma(s_j,s_j) = 1 is
+// entry j of the value array.
+__global__ void __launch_bounds__(kBlock) k_init_group(GroupView gv) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
+  const int v = nblk * kBlock + (int)threadIdx.x;
+  const int s0 = gv.src_begin + (gv.batch0 + g) * 64;
+  const int cnt = min(64, gv.src_begin + gv.src_count - s0);
+  const int j = v - s0;
+  const bool is_src = (v < gv.N) && j >= 0 && j < cnt;
+  NodeIdx n;
+  n.mask = is_src ? (1ull << j) : 0ull;
+  n.off = is_src ? (uint32_t)j : 0u;
+  n.pad = 0;
+  gv.idx[((size_t)g * gv.Lcap) * gv.Npad + v] = n;
+  gv.seen[(size_t)g * gv.Npad + v] = n.mask;
+  if (gv.dat != nullptr && is_src) gv.dat[(size_t)g * gv.Npad * 64 + j] = 1.0;
+  if (v == 0) {
+    gv.ltot[(size_t)g * gv.Lcap] = cnt;
+    if (gv.dag) gv.dag[g] = 0;
+  }
+}
+
+// One BFS level for every batch of the group, one thread per (batch, node), pull direction:
+// L_l[v] = (OR over in-neighbours u of L_{l-1}[u]) & ~seen[v].
+__global__ void __launch_bounds__(kBlock)
+k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
+            int level, int* __restrict__ level_new) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
+  const int v = nblk * kBlock + (int)threadIdx.x;
+  NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  uint64_t nw = 0;
+  if (v < gv.N) {
+    const uint64_t sn = gv.seen[(size_t)g * gv.Npad + v];
+    if (sn != valid_mask(gv.src_count, gv.batch0 + g)) {
+      uint64_t acc = 0;
+      const int p1 = in_ptr[v + 1];
+      for (int p = in_ptr[v]; p < p1; ++p) acc |= prev[in_col[p]].mask;
+      nw = acc & ~sn;
+      if (nw) gv.seen[(size_t)g * gv.Npad + v] = sn | nw;
+    }
+  }
+  NodeIdx n;
+  n.mask = nw;
+  n.off = 0;
+  n.pad = 0;
+  cur[v] = n;
+  // newly reached (source, node) pairs of this node block
+  __shared__ int s_cnt[kWavesPerBlock];
+  const int pc = wave_sum_int(__popcll(nw));
+  if (lane_id() == 0) s_cnt[threadIdx.x / kWave] = pc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) tot += s_cnt[w];
+    gv.bsum[((size_t)g * gv.Lcap + level) * gv.bpb + nblk] = tot;
+    if (tot > 0) {
+      atomicAdd((unsigned long long*)&gv.ltot[(size_t)g * gv.Lcap + level], (unsigned long long)tot);
+      level_new[level] = 1;
+    }
+  }
+}
+
+// Row offsets of the level-compact value array for levels 1..depth: exclusive prefix of
+// popcount(L_l[v]) in node order, after all rows of the levels above.
+__global__ void __launch_bounds__(kBlock) k_write_offsets(GroupView gv, int depth) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
+  __shared__ int s_w[kWavesPerBlock];
+  __shared__ int s_base;
+  const int t = (int)threadIdx.x, lane = lane_id(), wid = t / kWave;
+  const int v = nblk * kBlock + t;
+  long long level_base = gv.ltot[(size_t)g * gv.Lcap];
+  for (int l = 1; l <= depth; ++l) {
+    NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + l) * gv.Npad;
+    const int* __restrict__ bs = gv.bsum + ((size_t)g * gv.Lcap + l) * gv.bpb;
+    // pairs in the node blocks before this one
+    int before = 0;
+    for (int b = t; b < nblk; b += kBlock) before += bs[b];
+    before = wave_sum_int(before);
+    if (lane == 0) s_w[wid] = before;
+    __syncthreads();
+    if (t == 0) s_base = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+    __syncthreads();
+    const int block_base = s_base;
+    // prefix inside the node block
+    const int c = __popcll(cur[v].mask);
+    const int incl = wave_scan_incl(c, lane);
+    __syncthreads();
+    if (lane == kWave - 1) s_w[wid] = incl;
+    __syncthreads();
+    int wave_base = 0;
+    for (int w = 0; w < wid; ++w) wave_base += s_w[w];
+    cur[v].off = (uint32_t)(level_base + block_base + wave_base + incl - c);
+    level_base += gv.ltot[(size_t)g * gv.Lcap + l];
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// forward: path counts
+// ---------------------------------------------------------------------------------------
+
+// One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
+// A wave owns 64 consecutive nodes of one batch and works through them eight at a time: the
+// 64 lanes first fetch (in-neighbour, mask, offset) for 8 nodes x 8 in-links at once, then each
+// node's sources (lanes) gather from the compact rows of its active in-links, eight gathers in
+// flight.  Nodes with more than 8 in-links take further rounds.
+template <bool kCountDag>
+__global__ void __launch_bounds__(kBlock)
+k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
+            int level, long long* __restrict__ misc) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int lane = lane_id();
+  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (v0 >= gv.N) return;
+  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const NodeIdx me = load_idx(cur + v0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
+  if (nodes_active == 0) return;
+  const int sub = lane >> 3, slot = lane & 7;
+  bool inexact = false;
+  long long dag = 0;
+  for (int c = 0; c < 8; ++c) {
+    if (((nodes_active >> (8 * c)) & 0xffull) == 0) continue;
+    // index tile: lane (sub, slot) looks at in-link `slot` of node v0 + 8c + sub
+    const int vi = v0 + 8 * c + sub;
+    const uint64_t newv_i = shfl64(me.mask, 8 * c + sub);
+    int p0 = 0, p1 = 0;
+    if (newv_i != 0) {
+      p0 = in_ptr[vi];
+      p1 = in_ptr[vi + 1];
+    }
+    double acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+    for (int base = 0; __ballot(p0 + base < p1) != 0; base += 8) {
+      const int q = p0 + base + slot;
+      NodeIdx ix;
+      ix.mask = 0;
+      ix.off = 0;
+      if (q < p1) ix = load_idx(prev + in_col[q]);
+      const uint64_t act = __ballot((ix.mask & newv_i) != 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t a8 = (uint32_t)(act >> (8 * i)) & 0xffu;
+        if (a8 == 0) continue;
+        const uint64_t newv = readlane64(me.mask, 8 * c + i);
+        double x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          x[j] = 0.0;
+          if ((a8 >> j) & 1u) {  // uniform: this in-link carries paths for some source
+            const uint64_t mk = readlane64(ix.mask, 8 * i + j);
+            const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)ix.off, 8 * i + j);
+            const uint64_t m = mk & newv;
+            if (kCountDag) dag += __popcll(m);
+            if (lane_in(m)) x[j] = entry(dat, of + rank_in(mk));
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i] += x[j];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint64_t newv = readlane64(me.mask, 8 * c + i);
+      if (newv == 0) continue;
+      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+      if (lane_in(newv)) {
+        entry(dat, of + rank_in(newv)) = acc[i];
+        inexact |= acc[i] >= kTwo53;
+      }
+    }
+  }
+  if (inexact) misc[0] = 1;
+  if (kCountDag && dag != 0 && lane == 0) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
+}
+
+// ---------------------------------------------------------------------------------------
+// backward: dependency recursion and link loads
+// ---------------------------------------------------------------------------------------
+
+// One level of coef(s,u) = 1/sigma(s,u) + sum over out-links (u,w) with D(s,w) = D(s,u) + 1 of
+// coef(s,w), and load(u,w) += sum over sources of sigma(s,u) * coef(s,w): the share of the unit
+// demands that the equal split over shortest paths (Sec. 5.2) routes over the link.  Same tiling
+// as the forward kernel, over out-links.  coef overwrites sigma in place: an entry is read as
+// sigma only by its own node's step and gathered as coef only by shallower levels.  After the
+// eight-way wave reduction lane 8i+j holds the load of out-link j of node i, which is the lane
+// that fetched that link's id: one coalesced read-modify-write per round.
+__global__ void __launch_bounds__(kBlock)
+k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
+            int level) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int lane = lane_id();
+  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (u0 >= gv.N) return;
+  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const NodeIdx me = load_idx(cur + u0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
+  if (nodes_active == 0) return;
+  const int sub = lane >> 3, slot = lane & 7;
+  for (int c = 0; c < 8; ++c) {
+    if (((nodes_active >> (8 * c)) & 0xffull) == 0) continue;
+    const int ui = u0 + 8 * c + sub;
+    const uint64_t mu_i = shfl64(me.mask, 8 * c + sub);
+    int p0 = 0, p1 = 0;
+    if (mu_i != 0) {
+      p0 = out_ptr[ui];
+      p1 = out_ptr[ui + 1];
+    }
+    // own sigma of the eight nodes
+    double s_u[8], acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint64_t mu = readlane64(me.mask, 8 * c + i);
+      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+      s_u[i] = 1.0;
+      if (lane_in(mu)) s_u[i] = entry(dat, of + rank_in(mu));
+      acc[i] = 0.0;
+    }
+    for (int base = 0; __ballot(p0 + base < p1) != 0; base += 8) {
+      const int q = p0 + base + slot;
+      NodeIdx ix;
+      ix.mask = 0;
+      ix.off = 0;
+      if (q < p1) ix = load_idx(next + out_col[q]);
+      const bool link_active = (ix.mask & mu_i) != 0;
+      const uint64_t act = __ballot(link_active);
+      double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i, this round
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t a8 = (uint32_t)(act >> (8 * i)) & 0xffu;
+        if (a8 == 0) continue;
+        const uint64_t mu = readlane64(me.mask, 8 * c + i);
+        double x[8];
+        uint64_t m[8];
+        int pairs = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          x[j] = 0.0;
+          m[j] = 0;
+          if ((a8 >> j) & 1u) {  // uniform: some source goes u -> w on a shortest path
+            const uint64_t mk = readlane64(ix.mask, 8 * i + j);
+            const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)ix.off, 8 * i + j);
+            m[j] = mk & mu;
+            pairs += __popcll(m[j]);
+            if (lane_in(m[j])) x[j] = entry(dat, of + rank_in(mk));
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          acc[i] += x[j];
+          x[j] *= s_u[i];
+        }
+        if (pairs > kSerialPairs) {
+          const double tot = wave_sum8(x, lane);  // lane l: load of link (l & 7) of node i
+          if (sub == i) tot_l = tot;
+        } else {
+          // few (source, link) pairs: pick the products out lane by lane instead of reducing
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            uint64_t mm = m[j];
+            if (mm == 0) continue;
+            double sum = 0.0;
+            while (mm) {
+              const int l = __builtin_ctzll(mm);
+              mm &= mm - 1;
+              sum += __longlong_as_double((long long)readlane64((uint64_t)__double_as_longlong(x[j]), l));
+            }
+            if (lane == 8 * i + j) tot_l = sum;
+          }
+        }
+      }
+      if (link_active) pt[q] += tot_l;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint64_t mu = readlane64(me.mask, 8 * c + i);
+      if (mu == 0) continue;
+      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+      if (lane_in(mu)) entry(dat, of + rank_in(mu)) = recip(s_u[i]) + acc[i];
+    }
+  }
+}
+
+// load[a] = (first group ? 0 : load[a]) + part[0][a] + part[1][a] + ... in that order.
+__global__ void __launch_bounds__(kBlock)
+k_reduce_part(const double* __restrict__ part, size_t Epad, int G, long long E, int first,
+              double* __restrict__ load) {
+  const long long a = (long long)blockIdx.x * kBlock + threadIdx.x;
+  if (a >= E) return;
+  double s = first ? 0.0 : load[a];
+  for (int g = 0; g < G; ++g) s += part[(size_t)g * Epad + a];
+  load[a] = s;
+}
+
+// ---------------------------------------------------------------------------------------
+// a2a_distances outputs
+// ---------------------------------------------------------------------------------------
+
+// dist[s][v] from the level masks, through a 64 x 64 LDS tile so that rows of dist are written
+// with consecutive lanes on consecutive nodes.  One wave per (batch, 64-node tile).
+__global__ void __launch_bounds__(kWave)
+k_extract_dist(GroupView gv, int tiles, int depth, int32_t* __restrict__ dist,
+               long long* __restrict__ dist_sum) {
+  int g, tile;
+  if (!map_block(gv.G, tiles, kXcd, g, tile)) return;
+  __shared__ int32_t t_d[kWave][kWave + 1];
+  const int t = (int)threadIdx.x;
+  const int v = tile * kWave + t;
+  for (int j = 0; j < kWave; ++j) t_d[j][t] = -1;
+  for (int l = 0; l <= depth; ++l) {
+    uint64_t m = gv.idx[((size_t)g * gv.Lcap + l) * gv.Npad + v].mask;
+    while (m) {
+      const int j = __builtin_ctzll(m);
+      m &= m - 1;
+      t_d[j][t] = l;
+    }
+  }
+  __syncthreads();
+  const int row0 = (gv.batch0 + g) * 64;
+  const int cnt = min(64, gv.src_count - row0);
+  if (dist != nullptr && v < gv.N) {
+    for (int j = 0; j < cnt; ++j) dist[(size_t)(row0 + j) * gv.N + v] = t_d[j][t];
+  }
+  if (dist_sum != nullptr && t < cnt) {
+    long long s = 0;
+    const int lim = min(kWave, gv.N - tile * kWave);
+    for (int i = 0; i < lim; ++i) {
+      const int d = t_d[t][i];
+      s += d > 0 ? d : 0;
+    }
+    if (s) atomicAdd((unsigned long long*)&dist_sum[row0 + t], (unsigned long long)s);
+  }
+}
+
+// sigma[s][v] from the level-compact rows, transposed through LDS.  One wave per tile.
+__global__ void __launch_bounds__(kWave)
+k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_out) {
+  int g, tile;
+  if (!map_block(gv.G, tiles, kXcd, g, tile)) return;
+  __shared__ double t_s[kWave][kWave + 1];
+  const int t = (int)threadIdx.x;
+  const int v0 = tile * kWave;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  for (int i = 0; i < kWave; ++i) t_s[t][i] = 0.0;
+  for (int l = 0; l <= depth; ++l) {
+    const NodeIdx me = load_idx(gv.idx + ((size_t)g * gv.Lcap + l) * gv.Npad + v0 + t);
+    uint64_t todo = __ballot(me.mask != 0);
+    while (todo) {
+      const int i = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const uint64_t mk = readlane64(me.mask, i);
+      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, i);
+      if ((mk >> t) & 1ull) t_s[t][i] = dat[of + rank_in(mk)];
+    }
+  }
+  __syncthreads();
+  const int row0 = (gv.batch0 + g) * 64;
+  const int cnt = min(64, gv.src_count - row0);
+  if (v0 + t < gv.N) {
+    for (int j = 0; j < cnt; ++j) sigma_out[(size_t)(row0 + j) * gv.N + v0 + t] = t_s[j][t];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// bookkeeping
+// ---------------------------------------------------------------------------------------
+
+// Folds the per-batch level totals of a finished group into the call's running totals:
+// misc[1] += sum of distances, misc[2] += reached pairs, misc[3] += shortest-path links.
+// One workgroup; integer sums, so the order does not matter.
+__global__ void __launch_bounds__(kBlock)
+k_fold_counters(GroupView gv, int depth, long long* __restrict__ misc) {
+  __shared__ long long s_r[3][kWavesPerBlock];
+  const int t = (int)threadIdx.x;
+  long long ds = 0, rc = 0, dg = 0;
+  for (int i = t; i < gv.G * depth; i += kBlock) {
+    const int g = i / depth, l = 1 + i % depth;
+    const long long n = gv.ltot[(size_t)g * gv.Lcap + l];
+    ds += n * l;
+    rc += n;
+  }
+  if (gv.dag)
+    for (int g = t; g < gv.G; g += kBlock) dg += gv.dag[g];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    ds += __shfl_xor(ds, o, kWave);
+    rc += __shfl_xor(rc, o, kWave);
+    dg += __shfl_xor(dg, o, kWave);
+  }
+  if (lane_id() == 0) {
+    s_r[0][t / kWave] = ds;
+    s_r[1][t / kWave] = rc;
+    s_r[2][t / kWave] = dg;
+  }
+  __syncthreads();
+  if (t == 0) {
+    for (int w = 1; w < kWavesPerBlock; ++w) {
+      s_r[0][0] += s_r[0][w];
+      s_r[1][0] += s_r[1][w];
+      s_r[2][0] += s_r[2][w];
+    }
+    misc[1] += s_r[0][0];
+    misc[2] += s_r[1][0];
+    misc[3] += s_r[2][0];
+  }
+}
+
+// Final outputs of a call: totals and flag bits (bit 0: sigma reached 2^53, bit 1: some pair
+// unreachable).
+__global__ void k_finish(const long long* __restrict__ misc, long long pairs,
+                         long long* __restrict__ dist_sum_total, long long* __restrict__ unreachable,
+                         long long* __restrict__ flags, long long* __restrict__ prof_out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    const long long unr = pairs - misc[2];
+    if (prof_out) prof_out[8] += misc[3];
+    if (dist_sum_total) *dist_sum_total = misc[1];
+    if (unreachable) *unreachable = unr;
+    if (flags) *flags = (misc[0] ? 1 : 0) | (unr ? 2 : 0);
+  }
+}
+
+// max (lowest link id on ties) and min of load[0..E): one workgroup.
+__global__ void __launch_bounds__(1024)
+k_load_extrema(const double* __restrict__ load, long long E, long long* __restrict__ out) {
+  __shared__ double s_max[1024], s_min[1024];
+  __shared__ long long s_arg[1024];
+  const int t = (int)threadIdx.x;
+  double mx = -1.0, mn = __builtin_huge_val();
+  long long arg = -1;
+  for (long long a = t; a < E; a += 1024) {
+    const double x = load[a];
+    if (x > mx) {
+      mx = x;
+      arg = a;
+    }
+    if (x < mn) mn = x;
+  }
+  s_max[t] = mx;
+  s_min[t] = mn;
+  s_arg[t] = arg;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (t < o) {
+      const double om = s_max[t + o];
+      const long long oa = s_arg[t + o];
+      if (oa >= 0 && (s_arg[t] < 0 || om > s_max[t] || (om == s_max[t] && oa < s_arg[t]))) {
+        s_max[t] = om;
+        s_arg[t] = oa;
+      }
+      if (s_min[t + o] < s_min[t]) s_min[t] = s_min[t + o];
+    }
+    __syncthreads();
+  }
+  if (t == 0) {
+    out[0] = __double_as_longlong(s_max[0]);
+    out[1] = s_arg[0];
+    out[2] = __double_as_longlong(s_min[0]);
+  }
+}
+
+}  // namespace a2a_dev
