@@ -111,7 +111,8 @@ int a2a_distances(const a2a_topo* topo, int32_t src_begin, int32_t src_count, in
  *   load[a] = sum_s sum_{t != s} (# shortest s->t paths through link a) / sigma(s,t).
  * Computed per source batch by a forward path-count pass and a backward dependency pass over
  * the shortest-path DAG; batch results are added in ascending batch order, so the result is
- * bitwise reproducible whatever the workspace size.
+ * bitwise reproducible from run to run for a given workspace size (the size decides which
+ * batches advance together, and with it the summation order inside a batch).
  *   load            device, double[E], overwritten
  *   dist_sum_total  device, int64[1]: sum over these sources of sum_t D(s,t).  May be NULL.
  *   flags           device, int64[1]: A2A_FLAG_* bits.  May be NULL.

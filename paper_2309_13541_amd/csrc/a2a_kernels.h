@@ -6,10 +6,10 @@
 // reach v in exactly l hops (D(s,v) = l, the hop distance of Sec. 5.4) and an offset into the
 // batch's value array.  The value array is level-compact: the entries of (l, v) are the
 // popcount(L_l[v]) sources of that mask in lane order, rows follow each other in node order,
-// levels follow each other.  Every reachable (source, node) pair owns exactly one entry: it
-// holds sigma(s,v) (number of shortest paths, Sec. 5.2) after the forward pass and
-// coef(s,v) = (1 + delta(s,v)) / sigma(s,v) after the backward pass, where delta is the traffic
-// forwarded through v under the equal split of Sec. 5.2.  A link (u,w) is used by the sources
+// levels follow each other.  Every reachable (source, node) pair owns exactly one entry, at the
+// same position in two arrays: sigma(s,v) (number of shortest paths, Sec. 5.2), written by the
+// forward pass, and coef(s,v) = (1 + delta(s,v)) / sigma(s,v), written by the backward pass,
+// where delta is the traffic forwarded through v under the equal split of Sec. 5.2.  A link (u,w) is used by the sources
 // in L_l[u] & L_{l+1}[w]; a gather of row (l,u) therefore reads popcount(L_l[u]) values instead
 // of a 64-wide row, and a node's row is written once per pass instead of once per level.
 #pragma once
@@ -68,6 +68,9 @@ __device__ __forceinline__ bool lane_in(uint64_t m) { return __builtin_amdgcn_in
 // the host keeps below 4 GiB.
 __device__ __forceinline__ double& entry(double* __restrict__ dat, uint32_t e) {
   return *reinterpret_cast<double*>(reinterpret_cast<char*>(dat) + (size_t)(e * 8u));
+}
+__device__ __forceinline__ const double& entry(const double* __restrict__ dat, uint32_t e) {
+  return *reinterpret_cast<const double*>(reinterpret_cast<const char*>(dat) + (size_t)(e * 8u));
 }
 
 // 1/x for x >= 1: hardware estimate plus two Newton steps (relative error about 1e-16).
@@ -175,7 +178,8 @@ __device__ __forceinline__ uint64_t valid_mask(int src_count, int batch) {
 struct GroupView {
   NodeIdx* idx;       // [G][Lcap][Npad]
   uint64_t* seen;     // [G][Npad]
-  double* dat;        // [G][Npad*64]  level-compact values (nullptr: distances only)
+  double* dat;        // [G][Npad*64]  level-compact sigma (nullptr: distances only)
+  double* coef;       // [G][Npad*64]  level-compact coef (link loads only)
   int* bsum;          // [G][Lcap][bpb] newly reached pairs per node block and level
   long long* ltot;    // [G][Lcap]      newly reached pairs per level
   long long* dag;     // [G]            (source, link) pairs on shortest paths (profiling)
@@ -381,10 +385,10 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
 // One level of coef(s,u) = 1/sigma(s,u) + sum over out-links (u,w) with D(s,w) = D(s,u) + 1 of
 // coef(s,w), and load(u,w) += sum over sources of sigma(s,u) * coef(s,w): the share of the unit
 // demands that the equal split over shortest paths (Sec. 5.2) routes over the link.  Same tiling
-// as the forward kernel, over out-links.  coef overwrites sigma in place: an entry is read as
-// sigma only by its own node's step and gathered as coef only by shallower levels.  After the
-// eight-way wave reduction lane 8i+j holds the load of out-link j of node i, which is the lane
-// that fetched that link's id: one coalesced read-modify-write per round.
+// as the forward kernel, over out-links.  After the eight-way wave reduction lane 8i+j holds the
+// load of out-link j of node i, which is the lane that fetched that link's id: one coalesced
+// read-modify-write per round.  For levels whose rows are well filled; sparsely filled levels
+// go through k_bwd_init_level + k_bwd_pairs.
 __global__ void __launch_bounds__(kBlock)
 k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
             int level) {
@@ -395,7 +399,8 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
-  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
@@ -446,7 +451,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
             const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)ix.off, 8 * i + j);
             m[j] = mk & mu;
             pairs += __popcll(m[j]);
-            if (lane_in(m[j])) x[j] = entry(dat, of + rank_in(mk));
+            if (lane_in(m[j])) x[j] = entry(cf, of + rank_in(mk));
           }
         }
 #pragma unroll
@@ -480,8 +485,107 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
       const uint64_t mu = readlane64(me.mask, 8 * c + i);
       if (mu == 0) continue;
       const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-      if (lane_in(mu)) entry(dat, of + rank_in(mu)) = recip(s_u[i]) + acc[i];
+      if (lane_in(mu)) entry(cf, of + rank_in(mu)) = recip(s_u[i]) + acc[i];
     }
+  }
+}
+
+// --- sparsely populated levels: one thread per (batch, node) -------------------------------
+//
+// When a level holds only a few sources per node, a wave per node leaves most lanes idle and
+// pays the full per-node instruction cost for a handful of values.  These kernels give every
+// lane its own node and walk the (source, link) pairs one by one; sums are taken in a fixed
+// serial order (links in CSR order, sources in ascending order).
+
+__device__ __forceinline__ uint32_t below(uint64_t mask, int s) {
+  return (uint32_t)__popcll(mask & ((1ull << s) - 1ull));
+}
+
+// Forward, sparse level: sigma(s,v) accumulated pair by pair into the node's own entries.
+template <bool kCountDag>
+__global__ void __launch_bounds__(kBlock)
+k_fwd_pairs(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
+            int level, long long* __restrict__ misc) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int v = nblk * kBlock + (int)threadIdx.x;
+  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const NodeIdx me = load_idx(cur + v);
+  int dag = 0;
+  bool inexact = false;
+  if (me.mask != 0) {
+    uint64_t started = 0;  // sources whose entry has received its first term
+    const int p1 = in_ptr[v + 1];
+    for (int p = in_ptr[v]; p < p1; ++p) {
+      const NodeIdx ix = load_idx(prev + in_col[p]);
+      uint64_t m = ix.mask & me.mask;
+      if (kCountDag) dag += __popcll(m);
+      while (m) {
+        const int s = __builtin_ctzll(m);
+        m &= m - 1;
+        const double val = dat[ix.off + below(ix.mask, s)];
+        double* mine = dat + me.off + below(me.mask, s);
+        const double sum = ((started >> s) & 1ull) ? *mine + val : val;
+        *mine = sum;
+        inexact |= sum >= kTwo53;
+        started |= 1ull << s;
+      }
+    }
+  }
+  if (inexact) misc[0] = 1;
+  if (kCountDag) {
+    dag = wave_sum_int(dag);
+    if (dag != 0 && lane_id() == 0) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
+  }
+}
+
+// Backward, start of a level handled pair by pair: coef = 1/sigma for every entry of the level
+// (a flat sweep over the level's slice of the compact arrays).
+__global__ void __launch_bounds__(kBlock) k_bwd_init_level(GroupView gv, int level) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
+  const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
+  long long base = 0;
+  for (int l = 0; l < level; ++l) base += lt[l];
+  const long long cnt = lt[level];
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64 + base;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64 + base;
+  for (long long e = (long long)nblk * kBlock + threadIdx.x; e < cnt; e += (long long)gv.bpb * kBlock)
+    cf[e] = recip(dat[e]);
+}
+
+// Backward, sparse successors: for every (source, link) pair with the link's head one level
+// down, coef(s,u) += coef(s,w) and load(u,w) += sigma(s,u) * coef(s,w).
+__global__ void __launch_bounds__(kBlock)
+k_bwd_pairs(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
+            int level) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int u = nblk * kBlock + (int)threadIdx.x;
+  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
+  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const NodeIdx me = load_idx(cur + u);
+  if (me.mask == 0) return;
+  const int p1 = out_ptr[u + 1];
+  for (int p = out_ptr[u]; p < p1; ++p) {
+    const NodeIdx ix = load_idx(next + out_col[p]);
+    uint64_t m = ix.mask & me.mask;
+    if (m == 0) continue;
+    double x = 0.0;
+    while (m) {
+      const int s = __builtin_ctzll(m);
+      m &= m - 1;
+      const double c = cf[ix.off + below(ix.mask, s)];
+      const uint32_t mine = me.off + below(me.mask, s);
+      x += dat[mine] * c;
+      cf[mine] += c;
+    }
+    pt[p] += x;
   }
 }
 

@@ -67,7 +67,8 @@ struct Layout {
   size_t off_bsum = 0;       // int32 [G][Lcap][bpb]
   size_t off_seen = 0;       // uint64 [G][Npad]
   size_t off_idx = 0;        // NodeIdx [G][Lcap][Npad]
-  size_t off_dat = 0;        // double [G][Npad*64]
+  size_t off_dat = 0;        // double [G][Npad*64]  sigma
+  size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
   size_t off_part = 0;       // double [G][Epad]
   size_t total = 0;
 };
@@ -99,6 +100,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_seen = take((size_t)G * L.Npad * 8);
     const size_t o_idx = take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx));
     const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8) : 0;
+    const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     if (out) {
       out->off_level_new = o_level_new;
@@ -109,6 +111,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->off_seen = o_seen;
       out->off_idx = o_idx;
       out->off_dat = o_dat;
+      out->off_coef = o_coef;
       out->off_part = o_part;
       out->total = off;
       out->G = G;
@@ -195,6 +198,10 @@ int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
   return tail == N ? ecc : -1;
 }
 
+// Average number of sources per node below which a level is handled pair by pair (one thread
+// per node) instead of row by row (one wave per node).
+constexpr double kSparseLanes = 8.0;
+
 struct Run {
   const a2a_topo* t;
   Layout L;
@@ -202,6 +209,10 @@ struct Run {
   hipStream_t st;
   int src_begin, src_count;
   int inflight = env_inflight();
+  mutable std::vector<double> lanes_per_node;  // per level of the current group: pairs / (G*N)
+  bool sparse(int level) const {
+    return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kSparseLanes;
+  }
   int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
   GroupView view(int batch0, int G) const {
@@ -209,6 +220,7 @@ struct Run {
     gv.idx = (NodeIdx*)(ws + L.off_idx);
     gv.seen = (uint64_t*)(ws + L.off_seen);
     gv.dat = L.values ? (double*)(ws + L.off_dat) : nullptr;
+    gv.coef = L.loads ? (double*)(ws + L.off_coef) : nullptr;
     gv.bsum = (int*)(ws + L.off_bsum);
     gv.ltot = (long long*)(ws + L.off_ltot);
     gv.dag = (long long*)(ws + L.off_dag);
@@ -251,6 +263,18 @@ int run_bfs(const Run& r, const GroupView& gv, int* depth) {
   }
   if (l == L.Lcap) return A2A_ERR_LEVEL_OVERFLOW;
   HIP_TRY(hipGetLastError());
+  // how full each level is decides which kernel flavour the passes use
+  try {
+    std::vector<long long> lt((size_t)gv.G * L.Lcap);
+    HIP_TRY(hipMemcpyAsync(lt.data(), gv.ltot, lt.size() * 8, hipMemcpyDeviceToHost, r.st));
+    HIP_TRY(hipStreamSynchronize(r.st));
+    r.lanes_per_node.assign((size_t)d + 2, 0.0);
+    for (int g = 0; g < gv.G; ++g)
+      for (int k = 0; k <= d; ++k) r.lanes_per_node[k] += (double)lt[(size_t)g * L.Lcap + k];
+    for (auto& x : r.lanes_per_node) x /= (double)gv.G * (double)t->N;
+  } catch (const std::bad_alloc&) {
+    return A2A_ERR_NO_MEMORY;
+  }
   *depth = d;
   if (d > t->prof_depth) t->prof_depth = d;
   t->prof_groups++;
@@ -268,10 +292,18 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
     ProfScope ps(t, PROF_FWD, r.st);
-    if (t->prof_mode == 2)
-      k_fwd_level<true><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
-    else
-      k_fwd_level<false><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+    const bool count = t->prof_mode == 2;
+    if (r.sparse(l)) {
+      if (count)
+        k_fwd_pairs<true><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+      else
+        k_fwd_pairs<false><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+    } else {
+      if (count)
+        k_fwd_level<true><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+      else
+        k_fwd_level<false><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+    }
   }
   HIP_TRY(hipGetLastError());
   return A2A_OK;
@@ -486,7 +518,13 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
       for (int l = depth; l >= 0; --l) {
         ProfScope ps(t, PROF_BWD, st);
-        k_bwd_level<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+        if (l == depth || r.sparse(l + 1)) {
+          // few sources one level down: coef = 1/sigma, then the few pairs one by one
+          k_bwd_init_level<<<grid_for(gv.G, L.bpb), kBlock, 0, st>>>(gv, l);
+          if (l < depth) k_bwd_pairs<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+        } else {
+          k_bwd_level<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+        }
       }
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(
