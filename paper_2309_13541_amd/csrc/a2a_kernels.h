@@ -157,9 +157,10 @@ __device__ __forceinline__ int wave_scan_incl(int x, int lane) {
 }
 
 // Workgroups go round-robin to the 8 XCDs, each with its own L2.  `inflight` consecutive
-// workgroups belong to `inflight` different batches; with inflight = 8 all workgroups of one
-// batch run on one XCD, so that the small per-level arrays of that batch (masks, offsets, the
-// rows of sparsely populated levels) stay in that XCD's L2 while its waves gather from them.
+// workgroups belong to `inflight` different batches (or super-batches); with inflight = 8 all
+// workgroups of one batch run on one XCD, so that the small per-level arrays of that batch
+// (masks, offsets, the rows of sparsely populated levels) stay in that XCD's L2 while its waves
+// gather from them.
 __device__ __forceinline__ bool map_block(int G, int blocks_per_batch, int inflight, int& g, int& nblk) {
   const unsigned blk = blockIdx.x;
   const unsigned x = blk % (unsigned)inflight;
@@ -171,87 +172,116 @@ __device__ __forceinline__ bool map_block(int G, int blocks_per_batch, int infli
 
 __device__ __forceinline__ uint64_t valid_mask(int src_count, int batch) {
   const int cnt = src_count - batch * 64;
-  return cnt >= 64 ? ~0ull : ((1ull << cnt) - 1ull);
+  return cnt >= 64 ? ~0ull : (cnt <= 0 ? 0ull : ((1ull << cnt) - 1ull));
 }
 
-// Everything a level kernel needs to find its batch's arrays.
+// The BFS works on super-batches of kSub batches: the masks of one node for the kSub batches
+// lie next to each other (64 bytes), so that the kSub lanes that look at the same in-neighbour
+// share one memory request.
+constexpr int kSub = 8;
+constexpr int kBfsBlock = 512;                   // threads: kBfsNodes nodes x kSub batches
+constexpr int kBfsNodes = kBfsBlock / kSub;      // 64 nodes per BFS workgroup
+constexpr int kBfsWaves = kBfsBlock / kWave;
+
+// Everything a level kernel needs to find its batch's arrays.  G batches; SB = ceil(G/kSub)
+// super-batches (batches past G exist only in the BFS arrays and stay empty).
 struct GroupView {
-  NodeIdx* idx;       // [G][Lcap][Npad]
-  uint64_t* seen;     // [G][Npad]
+  uint64_t* bm;       // [SB][Lcap][Npad][kSub] BFS level masks L_l[v]
+  uint64_t* seen;     // [SB][Npad][kSub]
+  NodeIdx* idx;       // [SB][Lcap][Npad][kSub] mask + row offset, for the thread-per-node kernels
+  NodeIdx* idxb;      // [G][Lcap][Npad]        the same per batch, for the wave-per-node kernels
+                      //                        (both nullptr: distances only)
   double* dat;        // [G][Npad*64]  level-compact sigma (nullptr: distances only)
   double* coef;       // [G][Npad*64]  level-compact coef (link loads only)
-  int* bsum;          // [G][Lcap][bpb] newly reached pairs per node block and level
-  long long* ltot;    // [G][Lcap]      newly reached pairs per level
+  int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level;
+                      //                       after k_scan_blocks: first entry of the block's rows
+  long long* ltot;    // [SB*kSub][Lcap]   newly reached pairs per level
   long long* dag;     // [G]            (source, link) pairs on shortest paths (profiling)
   double* part;       // [G][Epad]      per-batch link loads
   size_t Epad;
-  int N, Npad, Lcap, G, bpb, inflight;
+  int N, Npad, Lcap, G, SB, bpb, nb64, inflight;
   int src_begin, src_count, batch0;
 };
+
+__device__ __forceinline__ size_t bm_at(const GroupView& gv, int sb, int level, int v, int k) {
+  return ((((size_t)sb * gv.Lcap + level) * gv.Npad) + v) * kSub + k;
+}
+
+// idx of batch sb*kSub+k at a level: element v is p[v * kSub].  The entries of one node for the
+// kSub batches of a super-batch share a 128-byte line: the kSub lanes that look at the same
+// node for different batches share the memory request.  The wave-per-node kernels, which work
+// on one batch per XCD at a time, use the per-batch copy idxb instead: a super-batch's level
+// (kSub times larger) would not stay in that XCD's L2.
+__device__ __forceinline__ NodeIdx* idx_level(const GroupView& gv, int sb, int level, int k) {
+  return gv.idx + bm_at(gv, sb, level, 0, k);
+}
 
 // ---------------------------------------------------------------------------------------
 // BFS
 // ---------------------------------------------------------------------------------------
 
 // Level 0: bit j of L_0[s_j] and seen[s_j] for the batch's sources s_j; sigma(s_j,s_j) = 1 is
-// entry j of the value array.
-__global__ void __launch_bounds__(kBlock) k_init_group(GroupView gv) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
-  const int v = nblk * kBlock + (int)threadIdx.x;
+// entry j of the value array.  One thread per (node, batch of the super-batch).
+__global__ void __launch_bounds__(kBfsBlock) k_init_group(GroupView gv) {
+  int sb, nblk;
+  if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
+  const int t = (int)threadIdx.x;
+  const int v = nblk * kBfsNodes + t / kSub, k = t % kSub;
+  const int g = sb * kSub + k;
   const int s0 = gv.src_begin + (gv.batch0 + g) * 64;
-  const int cnt = min(64, gv.src_begin + gv.src_count - s0);
+  // batches past the group's last one only pad the super-batch: no sources
+  const int cnt = g < gv.G ? max(0, min(64, gv.src_begin + gv.src_count - s0)) : 0;
   const int j = v - s0;
   const bool is_src = (v < gv.N) && j >= 0 && j < cnt;
-  NodeIdx n;
-  n.mask = is_src ? (1ull << j) : 0ull;
-  n.off = is_src ? (uint32_t)j : 0u;
-  n.pad = 0;
-  gv.idx[((size_t)g * gv.Lcap) * gv.Npad + v] = n;
-  gv.seen[(size_t)g * gv.Npad + v] = n.mask;
+  const uint64_t bit = is_src ? (1ull << j) : 0ull;
+  gv.bm[bm_at(gv, sb, 0, v, k)] = bit;
+  gv.seen[((size_t)sb * gv.Npad + v) * kSub + k] = bit;
   if (gv.dat != nullptr && is_src) gv.dat[(size_t)g * gv.Npad * 64 + j] = 1.0;
   if (v == 0) {
     gv.ltot[(size_t)g * gv.Lcap] = cnt;
-    if (gv.dag) gv.dag[g] = 0;
+    if (g < gv.G) gv.dag[g] = 0;
   }
 }
 
-// One BFS level for every batch of the group, one thread per (batch, node), pull direction:
+// One BFS level for every batch of the group, pull direction:
 // L_l[v] = (OR over in-neighbours u of L_{l-1}[u]) & ~seen[v].
-__global__ void __launch_bounds__(kBlock)
+// Thread (node, k): the kSub lanes of a node read the same in-link list and adjacent masks.
+__global__ void __launch_bounds__(kBfsBlock)
 k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
             int level, int* __restrict__ level_new) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
-  const int v = nblk * kBlock + (int)threadIdx.x;
-  NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
-  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  int sb, nblk;
+  if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
+  const int t = (int)threadIdx.x;
+  const int v = nblk * kBfsNodes + t / kSub, k = t % kSub;
+  const int g = sb * kSub + k;
+  const uint64_t* __restrict__ prev = gv.bm + bm_at(gv, sb, level - 1, 0, k);
   uint64_t nw = 0;
   if (v < gv.N) {
-    const uint64_t sn = gv.seen[(size_t)g * gv.Npad + v];
-    if (sn != valid_mask(gv.src_count, gv.batch0 + g)) {
+    const size_t si = ((size_t)sb * gv.Npad + v) * kSub + k;
+    const uint64_t sn = gv.seen[si];
+    const uint64_t valid = g < gv.G ? valid_mask(gv.src_count, gv.batch0 + g) : 0ull;
+    if (sn != valid) {
       uint64_t acc = 0;
       const int p1 = in_ptr[v + 1];
-      for (int p = in_ptr[v]; p < p1; ++p) acc |= prev[in_col[p]].mask;
+      for (int p = in_ptr[v]; p < p1; ++p) acc |= prev[(size_t)in_col[p] * kSub];
       nw = acc & ~sn;
-      if (nw) gv.seen[(size_t)g * gv.Npad + v] = sn | nw;
+      if (nw) gv.seen[si] = sn | nw;
     }
   }
-  NodeIdx n;
-  n.mask = nw;
-  n.off = 0;
-  n.pad = 0;
-  cur[v] = n;
-  // newly reached (source, node) pairs of this node block
-  __shared__ int s_cnt[kWavesPerBlock];
-  const int pc = wave_sum_int(__popcll(nw));
-  if (lane_id() == 0) s_cnt[threadIdx.x / kWave] = pc;
+  gv.bm[bm_at(gv, sb, level, v, k)] = nw;
+  // newly reached (source, node) pairs of this 64-node block, per batch
+  __shared__ int s_cnt[kSub];
+  if (t < kSub) s_cnt[t] = 0;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int tot = 0;
-#pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) tot += s_cnt[w];
-    gv.bsum[((size_t)g * gv.Lcap + level) * gv.bpb + nblk] = tot;
+  int pc = __popcll(nw);
+  pc += __shfl_xor(pc, 8, kWave);
+  pc += __shfl_xor(pc, 16, kWave);
+  pc += __shfl_xor(pc, 32, kWave);
+  if (lane_id() < kSub && pc != 0) atomicAdd(&s_cnt[k], pc);
+  __syncthreads();
+  if (t < kSub) {
+    const int tot = s_cnt[t];
+    gv.bsum[((size_t)g * gv.Lcap + level) * gv.nb64 + nblk] = tot;
     if (tot > 0) {
       atomicAdd((unsigned long long*)&gv.ltot[(size_t)g * gv.Lcap + level], (unsigned long long)tot);
       level_new[level] = 1;
@@ -259,38 +289,65 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   }
 }
 
-// Row offsets of the level-compact value array for levels 1..depth: exclusive prefix of
-// popcount(L_l[v]) in node order, after all rows of the levels above.
-__global__ void __launch_bounds__(kBlock) k_write_offsets(GroupView gv, int depth) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
-  __shared__ int s_w[kWavesPerBlock];
-  __shared__ int s_base;
-  const int t = (int)threadIdx.x, lane = lane_id(), wid = t / kWave;
-  const int v = nblk * kBlock + t;
-  long long level_base = gv.ltot[(size_t)g * gv.Lcap];
-  for (int l = 1; l <= depth; ++l) {
-    NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + l) * gv.Npad;
-    const int* __restrict__ bs = gv.bsum + ((size_t)g * gv.Lcap + l) * gv.bpb;
-    // pairs in the node blocks before this one
-    int before = 0;
-    for (int b = t; b < nblk; b += kBlock) before += bs[b];
-    before = wave_sum_int(before);
-    if (lane == 0) s_w[wid] = before;
-    __syncthreads();
-    if (t == 0) s_base = s_w[0] + s_w[1] + s_w[2] + s_w[3];
-    __syncthreads();
-    const int block_base = s_base;
-    // prefix inside the node block
-    const int c = __popcll(cur[v].mask);
+// bsum[g][l][*] (pairs per 64-node block) -> position of the block's first row in the batch's
+// value array: exclusive prefix over blocks, after all rows of the levels above.  One wave per
+// (batch, level), levels 1..depth.
+__global__ void __launch_bounds__(kWave) k_scan_blocks(GroupView gv, int depth) {
+  const int g = (int)blockIdx.x / depth, level = 1 + (int)blockIdx.x % depth;
+  const int lane = lane_id();
+  const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
+  long long carry = 0;
+  for (int l = 0; l < level; ++l) carry += lt[l];
+  int* __restrict__ bs = gv.bsum + ((size_t)g * gv.Lcap + level) * gv.nb64;
+  for (int b0 = 0; b0 < gv.nb64; b0 += kWave) {
+    const int b = b0 + lane;
+    const int c = b < gv.nb64 ? bs[b] : 0;
     const int incl = wave_scan_incl(c, lane);
+    if (b < gv.nb64) bs[b] = (int)(carry + incl - c);
+    carry += __shfl(incl, kWave - 1, kWave);
+  }
+}
+
+// Index arrays from the BFS masks: idx[sb][l][v][k] = { L_l[v], first entry of the row }.
+// Thread (node, k) as in the BFS; the row offsets are an exclusive prefix over nodes for each
+// batch k (three shuffle steps across the 8 nodes of a wave, then across the 8 waves via LDS).
+__global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int depth) {
+  int sb, nblk;
+  if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
+  __shared__ int s_w[kBfsWaves][kSub];
+  __shared__ NodeIdx s_n[kSub][kBfsNodes + 1];
+  const int t = (int)threadIdx.x, lane = lane_id(), wid = t / kWave;
+  const int v = nblk * kBfsNodes + t / kSub, k = t % kSub;
+  const int g = sb * kSub + k;
+  for (int l = 0; l <= depth; ++l) {
+    const uint64_t m = gv.bm[bm_at(gv, sb, l, v, k)];
+    NodeIdx n;
+    n.mask = m;
+    n.pad = 0;
+    if (l == 0) {
+      n.off = m ? (uint32_t)__builtin_ctzll(m) : 0u;  // source j owns entry j
+    } else {
+      const int c = __popcll(m);
+      int x = c;  // inclusive prefix over the wave's nodes, per batch
+      int y = __shfl_up(x, 8, kWave);
+      if (lane >= 8) x += y;
+      y = __shfl_up(x, 16, kWave);
+      if (lane >= 16) x += y;
+      y = __shfl_up(x, 32, kWave);
+      if (lane >= 32) x += y;
+      if (lane >= kWave - kSub) s_w[wid][k] = x;
+      __syncthreads();
+      int base = g < gv.G ? gv.bsum[((size_t)g * gv.Lcap + l) * gv.nb64 + nblk] : 0;
+      for (int w = 0; w < wid; ++w) base += s_w[w][k];
+      n.off = (uint32_t)(base + x - c);
+      __syncthreads();
+    }
+    gv.idx[bm_at(gv, sb, l, v, k)] = n;
+    // per-batch copy: wave w writes the 64 consecutive entries of batch sb*kSub+w
+    s_n[k][t / kSub] = n;
     __syncthreads();
-    if (lane == kWave - 1) s_w[wid] = incl;
-    __syncthreads();
-    int wave_base = 0;
-    for (int w = 0; w < wid; ++w) wave_base += s_w[w];
-    cur[v].off = (uint32_t)(level_base + block_base + wave_base + incl - c);
-    level_base += gv.ltot[(size_t)g * gv.Lcap + l];
+    const int gw = sb * kSub + wid;
+    if (gw < gv.G) gv.idxb[((size_t)gw * gv.Lcap + l) * gv.Npad + nblk * kBfsNodes + lane] = s_n[wid][lane];
     __syncthreads();
   }
 }
@@ -313,7 +370,7 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   const int lane = lane_id();
   const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (v0 >= gv.N) return;
-  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   const NodeIdx me = load_idx(cur + v0 + lane);
@@ -397,7 +454,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   const int lane = lane_id();
   const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (u0 >= gv.N) return;
-  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
   const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
@@ -503,23 +560,24 @@ __device__ __forceinline__ uint32_t below(uint64_t mask, int s) {
 
 // Forward, sparse level: sigma(s,v) accumulated pair by pair into the node's own entries.
 template <bool kCountDag>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBfsBlock)
 k_fwd_pairs(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
             int level, long long* __restrict__ misc) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
-  const int v = nblk * kBlock + (int)threadIdx.x;
-  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
-  const NodeIdx* __restrict__ prev = cur - gv.Npad;
-  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
-  const NodeIdx me = load_idx(cur + v);
+  int sb, nblk;
+  if (!map_block(gv.SB, gv.nb64, gv.inflight, sb, nblk)) return;
+  const int v = nblk * kBfsNodes + (int)threadIdx.x / kSub, k = (int)threadIdx.x % kSub;
+  const int g = sb * kSub + k;
+  const NodeIdx* __restrict__ cur = idx_level(gv, sb, level, k);
+  const NodeIdx* __restrict__ prev = idx_level(gv, sb, level - 1, k);
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;  // not touched if g >= G: no masks
+  const NodeIdx me = load_idx(cur + (size_t)v * kSub);
   int dag = 0;
   bool inexact = false;
   if (me.mask != 0) {
     uint64_t started = 0;  // sources whose entry has received its first term
     const int p1 = in_ptr[v + 1];
     for (int p = in_ptr[v]; p < p1; ++p) {
-      const NodeIdx ix = load_idx(prev + in_col[p]);
+      const NodeIdx ix = load_idx(prev + (size_t)in_col[p] * kSub);
       uint64_t m = ix.mask & me.mask;
       if (kCountDag) dag += __popcll(m);
       while (m) {
@@ -535,45 +593,50 @@ k_fwd_pairs(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     }
   }
   if (inexact) misc[0] = 1;
-  if (kCountDag) {
-    dag = wave_sum_int(dag);
-    if (dag != 0 && lane_id() == 0) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
+  if (kCountDag) {  // lanes with the same k sum up: lane k of the wave adds for batch k
+    dag += __shfl_xor(dag, 8, kWave);
+    dag += __shfl_xor(dag, 16, kWave);
+    dag += __shfl_xor(dag, 32, kWave);
+    if (dag != 0 && lane_id() < kSub) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
   }
 }
 
 // Backward, start of a level handled pair by pair: coef = 1/sigma for every entry of the level
 // (a flat sweep over the level's slice of the compact arrays).
-__global__ void __launch_bounds__(kBlock) k_bwd_init_level(GroupView gv, int level) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, kXcd, g, nblk)) return;
+__global__ void __launch_bounds__(kBfsBlock) k_bwd_init_level(GroupView gv, int level) {
+  int sb, nblk;
+  if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
+  const int g = sb * kSub + (int)threadIdx.x / kWave;  // wave k sweeps batch k's slice
+  if (g >= gv.G) return;
   const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
   long long base = 0;
   for (int l = 0; l < level; ++l) base += lt[l];
   const long long cnt = lt[level];
   const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64 + base;
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64 + base;
-  for (long long e = (long long)nblk * kBlock + threadIdx.x; e < cnt; e += (long long)gv.bpb * kBlock)
+  for (long long e = (long long)nblk * kWave + lane_id(); e < cnt; e += (long long)gv.nb64 * kWave)
     cf[e] = recip(dat[e]);
 }
 
 // Backward, sparse successors: for every (source, link) pair with the link's head one level
 // down, coef(s,u) += coef(s,w) and load(u,w) += sigma(s,u) * coef(s,w).
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBfsBlock)
 k_bwd_pairs(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
             int level) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
-  const int u = nblk * kBlock + (int)threadIdx.x;
-  const NodeIdx* __restrict__ cur = gv.idx + ((size_t)g * gv.Lcap + level) * gv.Npad;
-  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  int sb, nblk;
+  if (!map_block(gv.SB, gv.nb64, gv.inflight, sb, nblk)) return;
+  const int u = nblk * kBfsNodes + (int)threadIdx.x / kSub, k = (int)threadIdx.x % kSub;
+  const int g = sb * kSub + k;
+  const NodeIdx* __restrict__ cur = idx_level(gv, sb, level, k);
+  const NodeIdx* __restrict__ next = idx_level(gv, sb, level + 1, k);
   const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
-  const NodeIdx me = load_idx(cur + u);
+  const NodeIdx me = load_idx(cur + (size_t)u * kSub);
   if (me.mask == 0) return;
   const int p1 = out_ptr[u + 1];
   for (int p = out_ptr[u]; p < p1; ++p) {
-    const NodeIdx ix = load_idx(next + out_col[p]);
+    const NodeIdx ix = load_idx(next + (size_t)out_col[p] * kSub);
     uint64_t m = ix.mask & me.mask;
     if (m == 0) continue;
     double x = 0.0;
@@ -616,7 +679,7 @@ k_extract_dist(GroupView gv, int tiles, int depth, int32_t* __restrict__ dist,
   const int v = tile * kWave + t;
   for (int j = 0; j < kWave; ++j) t_d[j][t] = -1;
   for (int l = 0; l <= depth; ++l) {
-    uint64_t m = gv.idx[((size_t)g * gv.Lcap + l) * gv.Npad + v].mask;
+    uint64_t m = gv.bm[bm_at(gv, g / kSub, l, v, g % kSub)];
     while (m) {
       const int j = __builtin_ctzll(m);
       m &= m - 1;
@@ -651,7 +714,7 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
   const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   for (int i = 0; i < kWave; ++i) t_s[t][i] = 0.0;
   for (int l = 0; l <= depth; ++l) {
-    const NodeIdx me = load_idx(gv.idx + ((size_t)g * gv.Lcap + l) * gv.Npad + v0 + t);
+    const NodeIdx me = load_idx(gv.idxb + ((size_t)g * gv.Lcap + l) * gv.Npad + v0 + t);
     uint64_t todo = __ballot(me.mask != 0);
     while (todo) {
       const int i = __builtin_ctzll(todo);

@@ -57,16 +57,20 @@ struct Layout {
   int G = 0;     // batches per group
   int Lcap = 0;  // level slots per batch (levels 0 .. Lcap-1)
   int Npad = 0;  // N rounded up to a multiple of 256
-  int bpb = 0;   // node blocks per batch
+  int bpb = 0;   // 256-node blocks per batch
+  int nb64 = 0;  // 64-node blocks per batch
+  int SB = 0;    // super-batches of kSub batches (BFS arrays)
   bool values = false, loads = false;
   size_t Epad = 0;
   size_t off_level_new = 0;  // int32 [Lcap]
   size_t off_misc = 0;       // int64 [8]: 0 sigma-inexact flag, 1 dist_sum, 2 reached pairs, 3 DAG links
   size_t off_ltot = 0;       // int64 [G][Lcap]
   size_t off_dag = 0;        // int64 [G]
-  size_t off_bsum = 0;       // int32 [G][Lcap][bpb]
-  size_t off_seen = 0;       // uint64 [G][Npad]
-  size_t off_idx = 0;        // NodeIdx [G][Lcap][Npad]
+  size_t off_bsum = 0;       // int32 [SB*kSub][Lcap][nb64]
+  size_t off_seen = 0;       // uint64 [SB][Npad][kSub]
+  size_t off_bm = 0;         // uint64 [SB][Lcap][Npad][kSub]
+  size_t off_idx = 0;        // NodeIdx [SB][Lcap][Npad][kSub] (with sigma / loads)
+  size_t off_idxb = 0;       // NodeIdx [G][Lcap][Npad]        (with sigma / loads)
   size_t off_dat = 0;        // double [G][Npad*64]  sigma
   size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
   size_t off_part = 0;       // double [G][Epad]
@@ -82,6 +86,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
   L.loads = (flags & A2A_WS_LOADS) != 0;
   L.Npad = (int)align_up((size_t)t->N, kBlock);
   L.bpb = L.Npad / kBlock;
+  L.nb64 = L.Npad / kBfsNodes;
   L.Lcap = t->level_bound + 2;
   L.Epad = align_up((size_t)(t->E > 0 ? t->E : 1), 32);
   const int nb = (src_count + 63) / 64;
@@ -94,11 +99,14 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     };
     const size_t o_level_new = take((size_t)L.Lcap * 4);
     const size_t o_misc = take(64);
-    const size_t o_ltot = take((size_t)G * L.Lcap * 8);
+    const size_t SB = (size_t)(G + kSub - 1) / kSub;
+    const size_t o_ltot = take(SB * kSub * L.Lcap * 8);
     const size_t o_dag = take((size_t)G * 8);
-    const size_t o_bsum = take((size_t)G * L.Lcap * L.bpb * 4);
-    const size_t o_seen = take((size_t)G * L.Npad * 8);
-    const size_t o_idx = take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx));
+    const size_t o_bsum = take(SB * kSub * L.Lcap * L.nb64 * 4);
+    const size_t o_seen = take(SB * L.Npad * kSub * 8);
+    const size_t o_bm = take(SB * L.Lcap * L.Npad * kSub * 8);
+    const size_t o_idx = L.values ? take(SB * L.Lcap * L.Npad * kSub * sizeof(NodeIdx)) : 0;
+    const size_t o_idxb = L.values ? take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx)) : 0;
     const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8) : 0;
     const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
@@ -109,7 +117,10 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->off_dag = o_dag;
       out->off_bsum = o_bsum;
       out->off_seen = o_seen;
+      out->off_bm = o_bm;
+      out->SB = (int)SB;
       out->off_idx = o_idx;
+      out->off_idxb = o_idxb;
       out->off_dat = o_dat;
       out->off_coef = o_coef;
       out->off_part = o_part;
@@ -217,7 +228,9 @@ struct Run {
   long long* misc() const { return (long long*)(ws + L.off_misc); }
   GroupView view(int batch0, int G) const {
     GroupView gv;
-    gv.idx = (NodeIdx*)(ws + L.off_idx);
+    gv.bm = (uint64_t*)(ws + L.off_bm);
+    gv.idx = L.values ? (NodeIdx*)(ws + L.off_idx) : nullptr;
+    gv.idxb = L.values ? (NodeIdx*)(ws + L.off_idxb) : nullptr;
     gv.seen = (uint64_t*)(ws + L.off_seen);
     gv.dat = L.values ? (double*)(ws + L.off_dat) : nullptr;
     gv.coef = L.loads ? (double*)(ws + L.off_coef) : nullptr;
@@ -230,7 +243,9 @@ struct Run {
     gv.Npad = L.Npad;
     gv.Lcap = L.Lcap;
     gv.G = G;
+    gv.SB = (G + kSub - 1) / kSub;
     gv.bpb = L.bpb;
+    gv.nb64 = L.nb64;
     gv.inflight = inflight;
     gv.src_begin = src_begin;
     gv.src_count = src_count;
@@ -244,17 +259,18 @@ int run_bfs(const Run& r, const GroupView& gv, int* depth) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
   HIP_TRY(hipMemsetAsync(r.level_new(), 0, (size_t)L.Lcap * 4, r.st));
-  HIP_TRY(hipMemsetAsync(gv.ltot, 0, (size_t)gv.G * L.Lcap * 8, r.st));
+  HIP_TRY(hipMemsetAsync(gv.ltot, 0, (size_t)gv.SB * kSub * L.Lcap * 8, r.st));
   {
     ProfScope ps(t, PROF_INIT, r.st);
-    k_init_group<<<grid_for(gv.G, L.bpb), kBlock, 0, r.st>>>(gv);
+    k_init_group<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv);
   }
   int d = 0;
   int l = 1;
   for (; l < L.Lcap; ++l) {
     {
       ProfScope ps(t, PROF_BFS, r.st);
-      k_bfs_level<<<grid_for(gv.G, L.bpb), kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.level_new());
+      k_bfs_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l,
+                                                                   r.level_new());
     }
     HIP_TRY(hipMemcpyAsync(t->h_pinned, r.level_new() + l, 4, hipMemcpyDeviceToHost, r.st));
     HIP_TRY(hipStreamSynchronize(r.st));
@@ -285,24 +301,26 @@ int run_bfs(const Run& r, const GroupView& gv, int* depth) {
 int run_fwd(const Run& r, const GroupView& gv, int depth) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
-  if (depth >= 1) {
+  {
     ProfScope ps(t, PROF_OFFSETS, r.st);
-    k_write_offsets<<<grid_for(gv.G, L.bpb), kBlock, 0, r.st>>>(gv, depth);
+    if (depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * depth), kWave, 0, r.st>>>(gv, depth);
+    k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, depth);
   }
-  const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
+  const unsigned grid = grid_for(gv.SB, L.nb64, r.inflight);  // thread-per-node kernels
+  const unsigned gridw = grid_for(gv.G, L.bpb, r.inflight);   // wave-per-node kernels
   for (int l = 1; l <= depth; ++l) {
     ProfScope ps(t, PROF_FWD, r.st);
     const bool count = t->prof_mode == 2;
     if (r.sparse(l)) {
       if (count)
-        k_fwd_pairs<true><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+        k_fwd_pairs<true><<<grid, kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
       else
-        k_fwd_pairs<false><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+        k_fwd_pairs<false><<<grid, kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
     } else {
       if (count)
-        k_fwd_level<true><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+        k_fwd_level<true><<<gridw, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
       else
-        k_fwd_level<false><<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+        k_fwd_level<false><<<gridw, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
     }
   }
   HIP_TRY(hipGetLastError());
@@ -515,15 +533,15 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (rc != A2A_OK) return rc;
     if (t->E > 0) {
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
-      const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
+      const unsigned grid = grid_for(gv.SB, L.nb64, r.inflight);
       for (int l = depth; l >= 0; --l) {
         ProfScope ps(t, PROF_BWD, st);
-        if (l == depth || r.sparse(l + 1)) {
-          // few sources one level down: coef = 1/sigma, then the few pairs one by one
-          k_bwd_init_level<<<grid_for(gv.G, L.bpb), kBlock, 0, st>>>(gv, l);
-          if (l < depth) k_bwd_pairs<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+        if (l == depth || (r.sparse(l) && r.sparse(l + 1))) {
+          // few sources here and one level down: coef = 1/sigma, then the pairs one by one
+          k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
+          if (l < depth) k_bwd_pairs<<<grid, kBfsBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
         } else {
-          k_bwd_level<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+          k_bwd_level<<<grid_for(gv.G, L.bpb, r.inflight), kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
         }
       }
       ProfScope ps(t, PROF_REDUCE, st);
