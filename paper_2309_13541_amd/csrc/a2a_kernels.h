@@ -27,7 +27,7 @@ constexpr int kXcd = 8;      // workgroups are dealt round-robin to 8 XCDs
 constexpr double kTwo53 = 9007199254740992.0;
 // Up to this many (source, link) pairs per node the backward kernel adds the products lane by
 // lane; beyond it the eight-way wave reduction is cheaper.
-constexpr int kSerialPairs = 16;
+constexpr int kSerialPairs = 6;
 
 // One node of one (batch, level): 16 bytes so that mask and offset arrive in one request.
 struct __align__(16) NodeIdx {
@@ -134,6 +134,28 @@ __device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
   const double keep = b2 ? z[1] : z[0];
   const double send = b2 ? z[0] : z[1];
   double w = keep + xor_lanes<4>(send);
+  w += xor_lanes<8>(w);
+  w += xor_lanes<16>(w);
+  w += xor_lanes<32>(w);
+  return w;
+}
+
+// The same sums through LDS: each lane stores its eight values (one row of 64 per value, rows
+// padded by one to spread the banks), lane l then adds the eight values of x[l & 7] that lanes
+// 8*(l>>3) .. 8*(l>>3)+7 stored, and three exchange steps add the eight partial sums.  Seven
+// plus three additions on the vector ALU instead of 4+2+1+3 select-and-add rounds; the moves
+// go through the LDS pipeline.  `buf` is this wave's kSum8Doubles doubles of LDS.
+constexpr int kSum8Row = kWave + 1;
+constexpr int kSum8Doubles = 8 * kSum8Row;
+__device__ __forceinline__ double wave_sum8_lds(const double (&x)[8], int lane, double* buf) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) buf[j * kSum8Row + lane] = x[j];
+  __builtin_amdgcn_wave_barrier();
+  const double* row = buf + (lane & 7) * kSum8Row + (lane & ~7);
+  double w = row[0];
+#pragma unroll
+  for (int r = 1; r < 8; ++r) w += row[r];
+  __builtin_amdgcn_wave_barrier();
   w += xor_lanes<8>(w);
   w += xor_lanes<16>(w);
   w += xor_lanes<32>(w);
@@ -356,11 +378,80 @@ __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int d
 // forward: path counts
 // ---------------------------------------------------------------------------------------
 
+// --- well-filled levels: one wave per (batch, node) -------------------------------------
+//
+// A wave owns 64 consecutive nodes of one batch; lane j = source j.  It works through the nodes
+// eight at a time ("group"): the 64 lanes first fetch (neighbour, mask, offset) for 8 nodes x 8
+// links at once (an "index tile": lane 8i+j looks at link j of node i), then each node's
+// sources gather from the compact rows of its links.  Three things keep enough memory requests
+// in flight: the neighbour ids of the group after next and the index tile of the next group are
+// requested while the current group is worked on, and the eight row gathers of node i+1 are
+// issued before the values of node i are used.  Nodes with more than 8 links take further,
+// unpipelined, rounds.
+
+struct Tile {
+  uint64_t mask;  // L[neighbour] of this lane's link (0: no link)
+  uint32_t off;   // its row offset
+};
+
+// In- or out-link range of the 64 nodes, one node per lane; nothing for nodes not on this level.
+struct LinkRange {
+  int p0, p1;
+};
+
+__device__ __forceinline__ int tile_request_col(const int32_t* __restrict__ col, const LinkRange& lr, int c,
+                                                int base, int lane, int& q) {
+  const int src = 8 * c + (lane >> 3);
+  const int p0 = __shfl(lr.p0, src, kWave), p1 = __shfl(lr.p1, src, kWave);
+  q = p0 + base + (lane & 7);
+  if (q >= p1) q = -1;
+  return q >= 0 ? col[q] : -1;
+}
+
+__device__ __forceinline__ Tile tile_request_idx(const NodeIdx* __restrict__ level, int nb) {
+  Tile t;
+  t.mask = 0;
+  t.off = 0;
+  if (nb >= 0) {
+    const NodeIdx n = load_idx(level + nb);
+    t.mask = n.mask;
+    t.off = n.off;
+  }
+  return t;
+}
+
+// Issues the (up to) eight row gathers of node i of the current tile: lanes in mk & want read
+// their entry of the link's row.  Returns the number of (source, link) pairs.
+__device__ __forceinline__ int gather8(const double* __restrict__ rows, const Tile& tile, int i, uint64_t want,
+                                       double (&x)[8], uint64_t (&m)[8]) {
+  int pairs = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint64_t mk = readlane64(tile.mask, 8 * i + j);
+    const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)tile.off, 8 * i + j);
+    m[j] = mk & want;
+    pairs += __popcll(m[j]);
+    x[j] = 0.0;
+    if (lane_in(m[j])) x[j] = entry(rows, of + rank_in(mk));
+  }
+  return pairs;
+}
+
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
-// A wave owns 64 consecutive nodes of one batch and works through them eight at a time: the
-// 64 lanes first fetch (in-neighbour, mask, offset) for 8 nodes x 8 in-links at once, then each
-// node's sources (lanes) gather from the compact rows of its active in-links, eight gathers in
-// flight.  Nodes with more than 8 in-links take further rounds.
+__device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, const NodeIdx& me, int node, const double (&x)[8]) {
+  double a = 0.0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) a += x[j];
+  const uint64_t newv = readlane64(me.mask, node);
+  const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
+  bool big = false;
+  if (lane_in(newv)) {
+    entry(dat, of + rank_in(newv)) = a;
+    big = a >= kTwo53;
+  }
+  return big;
+}
+
 template <bool kCountDag>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
@@ -376,60 +467,57 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  const int sub = lane >> 3, slot = lane & 7;
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (me.mask != 0) {
+    lr.p0 = in_ptr[v0 + lane];
+    lr.p1 = in_ptr[v0 + lane + 1];
+  }
   bool inexact = false;
   long long dag = 0;
+  int q;
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
+  int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
+#pragma unroll 1
   for (int c = 0; c < 8; ++c) {
-    if (((nodes_active >> (8 * c)) & 0xffull) == 0) continue;
-    // index tile: lane (sub, slot) looks at in-link `slot` of node v0 + 8c + sub
-    const int vi = v0 + 8 * c + sub;
-    const uint64_t newv_i = shfl64(me.mask, 8 * c + sub);
-    int p0 = 0, p1 = 0;
-    if (newv_i != 0) {
-      p0 = in_ptr[vi];
-      p1 = in_ptr[vi + 1];
-    }
-    double acc[8];
+    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
+    nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+      double xa[8], xb[8];
+      uint64_t m[8];
+      int pairs = gather8(dat, tile, 0, readlane64(me.mask, 8 * c), xa, m);
+#pragma unroll 1
+      for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
+        pairs += gather8(dat, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
+        inexact |= fwd_finish(dat, me, 8 * c + i, xa);
+        if (i + 2 < 8) pairs += gather8(dat, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
+        inexact |= fwd_finish(dat, me, 8 * c + i + 1, xb);
+      }
+      if (kCountDag) dag += pairs;
+      // nodes with more than eight in-links: add the rest to the stored entries
+      const int p0 = __shfl(lr.p0, 8 * c + (lane >> 3), kWave), p1 = __shfl(lr.p1, 8 * c + (lane >> 3), kWave);
+      for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
+        const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
+#pragma unroll 1
+        for (int i = 0; i < 8; ++i) {
+          const uint64_t newv = readlane64(me.mask, 8 * c + i);
+          const int np = gather8(dat, extra, i, newv, xa, m);
+          if (np == 0) continue;
+          if (kCountDag) dag += np;
+          double a = 0.0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
-    for (int base = 0; __ballot(p0 + base < p1) != 0; base += 8) {
-      const int q = p0 + base + slot;
-      NodeIdx ix;
-      ix.mask = 0;
-      ix.off = 0;
-      if (q < p1) ix = load_idx(prev + in_col[q]);
-      const uint64_t act = __ballot((ix.mask & newv_i) != 0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t a8 = (uint32_t)(act >> (8 * i)) & 0xffu;
-        if (a8 == 0) continue;
-        const uint64_t newv = readlane64(me.mask, 8 * c + i);
-        double x[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          x[j] = 0.0;
-          if ((a8 >> j) & 1u) {  // uniform: this in-link carries paths for some source
-            const uint64_t mk = readlane64(ix.mask, 8 * i + j);
-            const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)ix.off, 8 * i + j);
-            const uint64_t m = mk & newv;
-            if (kCountDag) dag += __popcll(m);
-            if (lane_in(m)) x[j] = entry(dat, of + rank_in(mk));
+          for (int j = 0; j < 8; ++j) a += xa[j];
+          const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+          if (lane_in(newv)) {
+            double& e = entry(dat, of + rank_in(newv));
+            a += e;
+            e = a;
+            inexact |= a >= kTwo53;
           }
         }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i] += x[j];
       }
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint64_t newv = readlane64(me.mask, 8 * c + i);
-      if (newv == 0) continue;
-      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-      if (lane_in(newv)) {
-        entry(dat, of + rank_in(newv)) = acc[i];
-        inexact |= acc[i] >= kTwo53;
-      }
-    }
+    tile = tile_next;
   }
   if (inexact) misc[0] = 1;
   if (kCountDag && dag != 0 && lane == 0) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
@@ -441,11 +529,63 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
 
 // One level of coef(s,u) = 1/sigma(s,u) + sum over out-links (u,w) with D(s,w) = D(s,u) + 1 of
 // coef(s,w), and load(u,w) += sum over sources of sigma(s,u) * coef(s,w): the share of the unit
-// demands that the equal split over shortest paths (Sec. 5.2) routes over the link.  Same tiling
-// as the forward kernel, over out-links.  After the eight-way wave reduction lane 8i+j holds the
-// load of out-link j of node i, which is the lane that fetched that link's id: one coalesced
-// read-modify-write per round.  For levels whose rows are well filled; sparsely filled levels
-// go through k_bwd_init_level + k_bwd_pairs.
+// demands that the equal split over shortest paths (Sec. 5.2) routes over the link.  After the
+// eight-way wave reduction lane 8i+j holds the load of out-link j of node i, which is the lane
+// that fetched that link's id: one coalesced read-modify-write of the batch's link loads per
+// group.
+__device__ __forceinline__ double link_sums(double (&x)[8], const uint64_t (&m)[8], int pairs, int i, int lane,
+                                            double tot_l, double* sum8_buf) {
+  if (pairs > kSerialPairs) {
+    const double tot = wave_sum8_lds(x, lane, sum8_buf);  // lane l: load of link (l & 7) of node i
+    if ((lane >> 3) == i) tot_l = tot;
+  } else {
+    // few (source, link) pairs: pick the products out lane by lane instead of reducing
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      uint64_t mm = m[j];
+      if (mm == 0) continue;
+      double sum = 0.0;
+      while (mm) {
+        const int l = __builtin_ctzll(mm);
+        mm &= mm - 1;
+        sum += __longlong_as_double((long long)readlane64((uint64_t)__double_as_longlong(x[j]), l));
+      }
+      if (lane == 8 * i + j) tot_l = sum;
+    }
+  }
+  return tot_l;
+}
+
+// Own sigma of a node (1 in lanes that are not on this level), requested together with the rows.
+__device__ __forceinline__ double own_sigma(const double* __restrict__ dat, const NodeIdx& me, int node) {
+  const uint64_t mu = readlane64(me.mask, node);
+  const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
+  double s = 1.0;
+  if (lane_in(mu)) s = entry(dat, of + rank_in(mu));
+  return s;
+}
+
+// coef of a node from its sigma and the gathered coef rows (x, overwritten by the products that
+// the link loads are made of); `add`: further round of a node with more than eight links.
+__device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const NodeIdx& me, int node, int i, double s,
+                                             double (&x)[8], const uint64_t (&m)[8], int pairs, bool add, int lane,
+                                             double tot_l, double* sum8_buf) {
+  double a = 0.0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a += x[j];
+    x[j] *= s;
+  }
+  const uint64_t mu = readlane64(me.mask, node);
+  const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
+  if (lane_in(mu)) {
+    double& e = entry(cf, of + rank_in(mu));
+    e = add ? e + a : recip(s) + a;
+  }
+  if (pairs != 0) tot_l = link_sums(x, m, pairs, i, lane, tot_l, sum8_buf);
+  return tot_l;
+}
+
 __global__ void __launch_bounds__(kBlock)
 k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
             int level) {
@@ -459,91 +599,64 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  __shared__ double s_sum8[kWavesPerBlock][kSum8Doubles];
+  double* sum8_buf = s_sum8[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  const int sub = lane >> 3, slot = lane & 7;
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (me.mask != 0) {
+    lr.p0 = out_ptr[u0 + lane];
+    lr.p1 = out_ptr[u0 + lane + 1];
+  }
+  int q, q_next, q_nn;
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
+  int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
+#pragma unroll 1
   for (int c = 0; c < 8; ++c) {
-    if (((nodes_active >> (8 * c)) & 0xffull) == 0) continue;
-    const int ui = u0 + 8 * c + sub;
-    const uint64_t mu_i = shfl64(me.mask, 8 * c + sub);
-    int p0 = 0, p1 = 0;
-    if (mu_i != 0) {
-      p0 = out_ptr[ui];
-      p1 = out_ptr[ui + 1];
-    }
-    // own sigma of the eight nodes
-    double s_u[8], acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint64_t mu = readlane64(me.mask, 8 * c + i);
-      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-      s_u[i] = 1.0;
-      if (lane_in(mu)) s_u[i] = entry(dat, of + rank_in(mu));
-      acc[i] = 0.0;
-    }
-    for (int base = 0; __ballot(p0 + base < p1) != 0; base += 8) {
-      const int q = p0 + base + slot;
-      NodeIdx ix;
-      ix.mask = 0;
-      ix.off = 0;
-      if (q < p1) ix = load_idx(next + out_col[q]);
-      const bool link_active = (ix.mask & mu_i) != 0;
-      const uint64_t act = __ballot(link_active);
-      double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i, this round
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t a8 = (uint32_t)(act >> (8 * i)) & 0xffu;
-        if (a8 == 0) continue;
-        const uint64_t mu = readlane64(me.mask, 8 * c + i);
-        double x[8];
-        uint64_t m[8];
-        int pairs = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          x[j] = 0.0;
-          m[j] = 0;
-          if ((a8 >> j) & 1u) {  // uniform: some source goes u -> w on a shortest path
-            const uint64_t mk = readlane64(ix.mask, 8 * i + j);
-            const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)ix.off, 8 * i + j);
-            m[j] = mk & mu;
-            pairs += __popcll(m[j]);
-            if (lane_in(m[j])) x[j] = entry(cf, of + rank_in(mk));
-          }
+    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+    nb_next = -1;
+    q_nn = -1;
+    if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+      double xa[8], xb[8];
+      uint64_t ma[8], mb[8];
+      double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i
+      double sa = own_sigma(dat, me, 8 * c), sb;
+      int pa = gather8(cf, tile, 0, readlane64(me.mask, 8 * c), xa, ma), pb;
+#pragma unroll 1
+      for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
+        sb = own_sigma(dat, me, 8 * c + i + 1);
+        pb = gather8(cf, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, mb);
+        tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, false, lane, tot_l, sum8_buf);
+        if (i + 2 < 8) {
+          sa = own_sigma(dat, me, 8 * c + i + 2);
+          pa = gather8(cf, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, ma);
         }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          acc[i] += x[j];
-          x[j] *= s_u[i];
-        }
-        if (pairs > kSerialPairs) {
-          const double tot = wave_sum8(x, lane);  // lane l: load of link (l & 7) of node i
-          if (sub == i) tot_l = tot;
-        } else {
-          // few (source, link) pairs: pick the products out lane by lane instead of reducing
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            uint64_t mm = m[j];
-            if (mm == 0) continue;
-            double sum = 0.0;
-            while (mm) {
-              const int l = __builtin_ctzll(mm);
-              mm &= mm - 1;
-              sum += __longlong_as_double((long long)readlane64((uint64_t)__double_as_longlong(x[j]), l));
-            }
-            if (lane == 8 * i + j) tot_l = sum;
-          }
-        }
+        tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, xb, mb, pb, false, lane, tot_l, sum8_buf);
       }
-      if (link_active) pt[q] += tot_l;
+      const uint64_t mu_lane = shfl64(me.mask, 8 * c + (lane >> 3));
+      if (q >= 0 && (tile.mask & mu_lane) != 0) pt[q] += tot_l;
+      // nodes with more than eight out-links: add the rest to the stored coef
+      const int p0 = __shfl(lr.p0, 8 * c + (lane >> 3), kWave), p1 = __shfl(lr.p1, 8 * c + (lane >> 3), kWave);
+      for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
+        int qe;
+        const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
+        tot_l = 0.0;
+#pragma unroll 1
+        for (int i = 0; i < 8; ++i) {
+          pa = gather8(cf, extra, i, readlane64(me.mask, 8 * c + i), xa, ma);
+          if (pa == 0) continue;
+          sa = own_sigma(dat, me, 8 * c + i);
+          tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, true, lane, tot_l, sum8_buf);
+        }
+        if (qe >= 0 && (extra.mask & mu_lane) != 0) pt[qe] += tot_l;
+      }
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint64_t mu = readlane64(me.mask, 8 * c + i);
-      if (mu == 0) continue;
-      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-      if (lane_in(mu)) entry(cf, of + rank_in(mu)) = recip(s_u[i]) + acc[i];
-    }
+    tile = tile_next;
+    q = q_next;
+    q_next = q_nn;
   }
 }
 
