@@ -20,22 +20,44 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
-def algorithmic_bytes(N, E, src, dag_links):
-    """Bytes the method has to move once per-batch state exceeds on-chip storage.
+KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd_level",
+               "fwd_pairs": "k_fwd_pairs", "bwd_rows": "k_bwd_level", "bwd_init": "k_bwd_init_level",
+               "bwd_pairs": "k_bwd_pairs", "reduce": "k_reduce_part"}
 
-    per (source, node) pair: level tag 1 B written + 1 B read, sigma 8 B written + 8 B read,
-    coef 8 B written = 26 B; per (source, shortest-path link): sigma gather 8 B + coef gather
-    8 B; per (batch, link): partial load written + read by the ordered reduction = 16 B.
-    Split by pass so that each kernel class can be priced on its own share.
+
+def algorithmic_bytes(prof, dag_level, nb, E, steps):
+    """Algorithmic bytes per kernel class for one step.
+
+    Per reachable (source, node) pair: level tag 1 B written (BFS) + 1 B read (forward),
+    sigma 8 B written (forward) + 8 B read (backward), coef 8 B written (backward) = 26 B.
+    Per (source, shortest-path link): sigma gather 8 B (forward) + coef gather 8 B (backward).
+    Per (batch, link): partial load 8 B written (backward, spread over its launches in
+    proportion to their links) + 8 B read (ordered reduction).
+    A launch at level l is charged the pairs of level l and the links into (forward) or out of
+    (backward) that level; which kernel class ran the level comes from the per-level timings.
     """
-    pairs = src * N
-    nb = (src + 63) // 64
-    return {
-        "bfs": 1 * pairs,
-        "fwd": (1 + 8) * pairs + 8 * dag_links,
-        "bwd": (8 + 8) * pairs + 8 * dag_links + 8 * nb * E,
-        "reduce": 8 * nb * E,
-    }
+    L = len(prof["pairs_level"])
+    pairs = [p / steps for p in prof["pairs_level"]]       # per step
+    dag_in = list(dag_level)                                # links into level l (one step)
+    dag_out = [dag_in[l + 1] if l + 1 < L else 0 for l in range(L)]
+    dag_total = max(sum(dag_in), 1)
+    ran = {k: [ms > 0 for ms in prof[k]["ms_level"]] for k in KERNEL_NAME}
+    out = {k: 0.0 for k in KERNEL_NAME}
+    for l in range(L):
+        if ran["bfs"][l]:
+            out["bfs"] += 1 * pairs[l]
+        for k in ("fwd_rows", "fwd_pairs"):
+            if ran[k][l]:
+                out[k] += (1 + 8) * pairs[l] + 8 * dag_in[l]
+        part = 8.0 * nb * E * dag_out[l] / dag_total
+        if ran["bwd_rows"][l]:
+            out["bwd_rows"] += (8 + 8) * pairs[l] + 8 * dag_out[l] + part
+        if ran["bwd_init"][l]:
+            out["bwd_init"] += (8 + 8) * pairs[l]
+        if ran["bwd_pairs"][l]:
+            out["bwd_pairs"] += 8 * dag_out[l] + part
+    out["reduce"] = 8.0 * nb * E
+    return out
 
 
 def read_traffic(kernel):
@@ -58,6 +80,9 @@ def main():
                     help="sources in the oracle's timed sample (default: sized for ~10-20 s)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--max-workspace-gib", type=float, default=None)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (sources would shard across GPUs with one "
@@ -87,6 +112,13 @@ def main():
         # sum_dist / flags stay on the device until the end; the bound needs Lmax only
         return topo.schedule_bound(load, 0, 0, 1.0, 1.0)[0]
 
+    if args.pmc_calibration:
+        src = torch.ones(2 ** 28, dtype=torch.float32, device="cuda")  # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -100,7 +132,8 @@ def main():
     # one more, untimed, step counts the (source, link) pairs on shortest paths
     topo.profile_enable(2)
     step()
-    dag = topo.profile_read()["dag_links"]
+    prof2 = topo.profile_read()
+    dag, dag_level = prof2["dag_links"], prof2["dag_level"]
     topo.profile_enable(0)
     sec = elapsed / args.steps
     sum_dist = int(dsum.item())
@@ -108,17 +141,18 @@ def main():
     bound, _ = topo.schedule_bound(load, sum_dist, fl, 1.0, 1.0, allow_disconnected=True)
 
     steps = args.steps
-    alg = algorithmic_bytes(N, E, N, dag)
-    per_class = {}
-    alg["offsets"] = 0
-    for k in ("bfs", "offsets", "fwd", "bwd", "reduce"):
+    nb = (N + 63) // 64
+    alg = algorithmic_bytes(prof, dag_level, nb, E, steps)
+    per_kernel = {}
+    for k, name in KERNEL_NAME.items():
         ms, n = prof[k]["ms"], prof[k]["launches"]
         if n:
-            per_class[k] = {"ms_per_step": ms / steps, "launches_per_step": n // steps,
-                            "avg_launch_ms": ms / n,
-                            "alg_GBps": alg[k] / (ms / steps * 1e-3) / 1e9 if ms > 0 else None}
-    dom = max(("bfs", "fwd", "bwd", "reduce"), key=lambda k: prof[k]["ms"])
-    kname = {"bfs": "k_bfs_level", "fwd": "k_fwd_level", "bwd": "k_bwd_level", "reduce": "k_reduce_part"}[dom]
+            per_kernel[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps,
+                                "avg_launch_ms": ms / n, "alg_GB_per_step": alg[k] / 1e9,
+                                "alg_GBps": alg[k] / (ms / steps * 1e-3) / 1e9 if ms > 0 else None,
+                                "traffic_bytes_per_launch": read_traffic(name)}
+    dom = max(KERNEL_NAME, key=lambda k: prof[k]["ms"])
+    kname = KERNEL_NAME[dom]
     n_l = prof[dom]["launches"]
     achieved = alg[dom] * steps / n_l / (prof[dom]["ms"] / n_l * 1e-3) / 1e9
     alg_total = sum(alg.values())
@@ -127,9 +161,10 @@ def main():
         "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kname),
         "alg_bytes_per_launch": alg[dom] * steps / n_l, "avg_launch_ms": prof[dom]["ms"] / n_l,
+        "launches_per_step": n_l / steps,
         "whole_path": {"alg_bytes": alg_total, "GBps": alg_total / sec / 1e9,
                        "frac": alg_total / sec / 1e9 / HBM_PEAK_GBPS},
-        "per_class": per_class,
+        "per_kernel": per_kernel,
     }
 
     cpu = None

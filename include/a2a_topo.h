@@ -163,15 +163,30 @@ int a2a_schedule_bound(const a2a_topo* topo, const double* load, int64_t sum_dis
  * a2a_profile_read waits for the device and sums the event times per kernel class; index
  * A2A_PROF_* into ms[] / launches[].  Not thread safe.
  */
-enum { A2A_PROF_INIT = 0, A2A_PROF_BFS, A2A_PROF_FWD, A2A_PROF_BWD, A2A_PROF_REDUCE, A2A_PROF_EXTRACT,
-       A2A_PROF_OFFSETS, A2A_PROF_CLASSES };
+typedef enum a2a_prof_kernel {
+  A2A_K_INIT = 0,  /* level 0 set-up */
+  A2A_K_BFS,       /* one BFS level */
+  A2A_K_OFFSETS,   /* row offsets of the level-compact arrays */
+  A2A_K_FWD_ROWS,  /* forward level, one wave per node (well-filled level) */
+  A2A_K_FWD_PAIRS, /* forward level, one thread per node (sparse level) */
+  A2A_K_BWD_ROWS,  /* backward level, one wave per node */
+  A2A_K_BWD_INIT,  /* backward level, coef = 1/sigma sweep before A2A_K_BWD_PAIRS */
+  A2A_K_BWD_PAIRS, /* backward level, one thread per node */
+  A2A_K_REDUCE,    /* ordered sum of the per-batch link loads */
+  A2A_K_EXTRACT,   /* dist / sigma output of a2a_distances */
+  A2A_K_COUNT
+} a2a_prof_kernel;
+#define A2A_PROF_MAX_LEVELS 64 /* deeper levels are lumped into the last slot */
 typedef struct a2a_profile {
-  double ms[8];        /* summed kernel time per class, milliseconds */
-  int64_t launches[8]; /* launches per class */
-  int64_t dag_links;   /* mode 2: sum over sources of links (u,w) with D(s,w) = D(s,u) + 1 */
-  int64_t calls;       /* a2a_distances + a2a_link_loads calls since enable */
-  int32_t depth;       /* deepest BFS level seen */
-  int32_t groups;      /* batch groups processed */
+  double ms[16];                               /* summed kernel time per a2a_prof_kernel, milliseconds */
+  int64_t launches[16];                        /* launches per a2a_prof_kernel */
+  double ms_level[16][A2A_PROF_MAX_LEVELS];    /* the same time split by BFS level */
+  int64_t pairs_level[A2A_PROF_MAX_LEVELS];    /* reachable (source, node) pairs per level, all calls */
+  int64_t dag_level[A2A_PROF_MAX_LEVELS];      /* mode 2: (source, link) pairs with D(s,w) = D(s,u)+1 = level */
+  int64_t dag_links;                           /* mode 2: sum of dag_level */
+  int64_t calls;                               /* a2a_distances + a2a_link_loads calls since enable */
+  int32_t depth;                               /* deepest BFS level seen */
+  int32_t groups;                              /* batch groups processed */
 } a2a_profile;
 int a2a_profile_enable(a2a_topo* topo, int mode);
 int a2a_profile_read(a2a_topo* topo, a2a_profile* out);

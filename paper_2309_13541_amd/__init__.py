@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     A2AError,
     Bound,
     Profile,
-    PROF_CLASSES,
+    PROF_KERNELS,
     Topology,
     build_library,
     library_path,

@@ -41,7 +41,9 @@ EXPORTED_SYMBOLS = (
     "a2a_profile_enable", "a2a_profile_read",
 )
 
-PROF_CLASSES = ("init", "bfs", "fwd", "bwd", "reduce", "extract", "offsets")
+PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_pairs", "bwd_rows", "bwd_init", "bwd_pairs",
+                "reduce", "extract")
+PROF_MAX_LEVELS = 64
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -71,15 +73,19 @@ class Bound(ctypes.Structure):
 
 class Profile(ctypes.Structure):
     """Mirror of ``a2a_profile``."""
-    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int64 * 8),
+    _fields_ = [("ms", ctypes.c_double * 16), ("launches", ctypes.c_int64 * 16),
+                ("ms_level", (ctypes.c_double * PROF_MAX_LEVELS) * 16),
+                ("pairs_level", ctypes.c_int64 * PROF_MAX_LEVELS),
+                ("dag_level", ctypes.c_int64 * PROF_MAX_LEVELS),
                 ("dag_links", ctypes.c_int64), ("calls", ctypes.c_int64),
                 ("depth", ctypes.c_int32), ("groups", ctypes.c_int32)]
 
     def as_dict(self) -> dict:
         d = {"dag_links": self.dag_links, "calls": self.calls, "depth": self.depth,
-             "groups": self.groups}
-        for i, n in enumerate(PROF_CLASSES):
-            d[n] = {"ms": self.ms[i], "launches": self.launches[i]}
+             "groups": self.groups, "pairs_level": list(self.pairs_level),
+             "dag_level": list(self.dag_level)}
+        for i, n in enumerate(PROF_KERNELS):
+            d[n] = {"ms": self.ms[i], "launches": self.launches[i], "ms_level": list(self.ms_level[i])}
         return d
 
 

@@ -218,7 +218,7 @@ struct GroupView {
   int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level;
                       //                       after k_scan_blocks: first entry of the block's rows
   long long* ltot;    // [SB*kSub][Lcap]   newly reached pairs per level
-  long long* dag;     // [G]            (source, link) pairs on shortest paths (profiling)
+  long long* dag;     // [G][Lcap]      (source, link) pairs into each level (profiling mode 2)
   double* part;       // [G][Epad]      per-batch link loads
   size_t Epad;
   int N, Npad, Lcap, G, SB, bpb, nb64, inflight;
@@ -261,7 +261,8 @@ __global__ void __launch_bounds__(kBfsBlock) k_init_group(GroupView gv) {
   if (gv.dat != nullptr && is_src) gv.dat[(size_t)g * gv.Npad * 64 + j] = 1.0;
   if (v == 0) {
     gv.ltot[(size_t)g * gv.Lcap] = cnt;
-    if (g < gv.G) gv.dag[g] = 0;
+    if (g < gv.G)
+      for (int l = 0; l < gv.Lcap; ++l) gv.dag[(size_t)g * gv.Lcap + l] = 0;
   }
 }
 
@@ -520,7 +521,8 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     tile = tile_next;
   }
   if (inexact) misc[0] = 1;
-  if (kCountDag && dag != 0 && lane == 0) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
+  if (kCountDag && dag != 0 && lane == 0)
+    atomicAdd((unsigned long long*)&gv.dag[(size_t)g * gv.Lcap + level], (unsigned long long)dag);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -710,7 +712,8 @@ k_fwd_pairs(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     dag += __shfl_xor(dag, 8, kWave);
     dag += __shfl_xor(dag, 16, kWave);
     dag += __shfl_xor(dag, 32, kWave);
-    if (dag != 0 && lane_id() < kSub) atomicAdd((unsigned long long*)&gv.dag[g], (unsigned long long)dag);
+    if (dag != 0 && lane_id() < kSub)
+      atomicAdd((unsigned long long*)&gv.dag[(size_t)g * gv.Lcap + level], (unsigned long long)dag);
   }
 }
 
@@ -850,42 +853,36 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
 // ---------------------------------------------------------------------------------------
 
 // Folds the per-batch level totals of a finished group into the call's running totals:
-// misc[1] += sum of distances, misc[2] += reached pairs, misc[3] += shortest-path links.
-// One workgroup; integer sums, so the order does not matter.
+// misc[1] += sum of distances, misc[2] += reached pairs.  One workgroup; integer sums, so the
+// order does not matter.
 __global__ void __launch_bounds__(kBlock)
 k_fold_counters(GroupView gv, int depth, long long* __restrict__ misc) {
-  __shared__ long long s_r[3][kWavesPerBlock];
+  __shared__ long long s_r[2][kWavesPerBlock];
   const int t = (int)threadIdx.x;
-  long long ds = 0, rc = 0, dg = 0;
+  long long ds = 0, rc = 0;
   for (int i = t; i < gv.G * depth; i += kBlock) {
     const int g = i / depth, l = 1 + i % depth;
     const long long n = gv.ltot[(size_t)g * gv.Lcap + l];
     ds += n * l;
     rc += n;
   }
-  if (gv.dag)
-    for (int g = t; g < gv.G; g += kBlock) dg += gv.dag[g];
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     ds += __shfl_xor(ds, o, kWave);
     rc += __shfl_xor(rc, o, kWave);
-    dg += __shfl_xor(dg, o, kWave);
   }
   if (lane_id() == 0) {
     s_r[0][t / kWave] = ds;
     s_r[1][t / kWave] = rc;
-    s_r[2][t / kWave] = dg;
   }
   __syncthreads();
   if (t == 0) {
     for (int w = 1; w < kWavesPerBlock; ++w) {
       s_r[0][0] += s_r[0][w];
       s_r[1][0] += s_r[1][w];
-      s_r[2][0] += s_r[2][w];
     }
     misc[1] += s_r[0][0];
     misc[2] += s_r[1][0];
-    misc[3] += s_r[2][0];
   }
 }
 
@@ -893,10 +890,9 @@ k_fold_counters(GroupView gv, int depth, long long* __restrict__ misc) {
 // unreachable).
 __global__ void k_finish(const long long* __restrict__ misc, long long pairs,
                          long long* __restrict__ dist_sum_total, long long* __restrict__ unreachable,
-                         long long* __restrict__ flags, long long* __restrict__ prof_out) {
+                         long long* __restrict__ flags) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     const long long unr = pairs - misc[2];
-    if (prof_out) prof_out[8] += misc[3];
     if (dist_sum_total) *dist_sum_total = misc[1];
     if (unreachable) *unreachable = unr;
     if (flags) *flags = (misc[0] ? 1 : 0) | (unr ? 2 : 0);

@@ -12,7 +12,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -36,11 +35,13 @@ struct a2a_topo {
   int64_t* d_small = nullptr;   // 16 x int64 device words (schedule_bound result, profile counters)
   // optional per-kernel timing (a2a_profile_enable); events are created per launch while it is on
   struct ProfRec {
-    int cls;
+    int cls, level;
     hipEvent_t beg, end;
   };
   mutable int prof_mode = 0;  // 0 off, 1 events, 2 events + shortest-path link count
   mutable std::vector<ProfRec> prof_recs;
+  mutable int64_t prof_pairs_level[A2A_PROF_MAX_LEVELS] = {};
+  mutable int64_t prof_dag_level[A2A_PROF_MAX_LEVELS] = {};
   mutable int64_t prof_calls = 0;
   mutable int32_t prof_depth = 0;
   mutable int32_t prof_groups = 0;
@@ -48,7 +49,12 @@ struct a2a_topo {
 
 namespace {
 
-enum { PROF_INIT = 0, PROF_BFS, PROF_FWD, PROF_BWD, PROF_REDUCE, PROF_EXTRACT, PROF_OFFSETS, PROF_CLASSES };
+enum {
+  PROF_INIT = A2A_K_INIT, PROF_BFS = A2A_K_BFS, PROF_OFFSETS = A2A_K_OFFSETS, PROF_FWD = A2A_K_FWD_ROWS,
+  PROF_FWD_PAIRS = A2A_K_FWD_PAIRS, PROF_BWD = A2A_K_BWD_ROWS, PROF_BWD_INIT = A2A_K_BWD_INIT,
+  PROF_BWD_PAIRS = A2A_K_BWD_PAIRS, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
+  PROF_CLASSES = A2A_K_COUNT
+};
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -65,7 +71,7 @@ struct Layout {
   size_t off_level_new = 0;  // int32 [Lcap]
   size_t off_misc = 0;       // int64 [8]: 0 sigma-inexact flag, 1 dist_sum, 2 reached pairs, 3 DAG links
   size_t off_ltot = 0;       // int64 [G][Lcap]
-  size_t off_dag = 0;        // int64 [G]
+  size_t off_dag = 0;        // int64 [G][Lcap]
   size_t off_bsum = 0;       // int32 [SB*kSub][Lcap][nb64]
   size_t off_seen = 0;       // uint64 [SB][Npad][kSub]
   size_t off_bm = 0;         // uint64 [SB][Lcap][Npad][kSub]
@@ -101,7 +107,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_misc = take(64);
     const size_t SB = (size_t)(G + kSub - 1) / kSub;
     const size_t o_ltot = take(SB * kSub * L.Lcap * 8);
-    const size_t o_dag = take((size_t)G * 8);
+    const size_t o_dag = take((size_t)G * L.Lcap * 8);
     const size_t o_bsum = take(SB * kSub * L.Lcap * L.nb64 * 4);
     const size_t o_seen = take(SB * L.Npad * kSub * 8);
     const size_t o_bm = take(SB * L.Lcap * L.Npad * kSub * 8);
@@ -162,9 +168,10 @@ struct ProfScope {
   hipStream_t st;
   a2a_topo::ProfRec rec{};
   bool live = false;
-  ProfScope(const a2a_topo* t_, int cls, hipStream_t st_) : t(t_), st(st_) {
+  ProfScope(const a2a_topo* t_, int cls, hipStream_t st_, int level = 0) : t(t_), st(st_) {
     if (t->prof_mode == 0) return;
     rec.cls = cls;
+    rec.level = level;
     if (hipEventCreate(&rec.beg) != hipSuccess) return;
     if (hipEventCreate(&rec.end) != hipSuccess) {
       (void)hipEventDestroy(rec.beg);
@@ -268,7 +275,7 @@ int run_bfs(const Run& r, const GroupView& gv, int* depth) {
   int l = 1;
   for (; l < L.Lcap; ++l) {
     {
-      ProfScope ps(t, PROF_BFS, r.st);
+      ProfScope ps(t, PROF_BFS, r.st, l);
       k_bfs_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l,
                                                                    r.level_new());
     }
@@ -287,6 +294,9 @@ int run_bfs(const Run& r, const GroupView& gv, int* depth) {
     r.lanes_per_node.assign((size_t)d + 2, 0.0);
     for (int g = 0; g < gv.G; ++g)
       for (int k = 0; k <= d; ++k) r.lanes_per_node[k] += (double)lt[(size_t)g * L.Lcap + k];
+    if (t->prof_mode)
+      for (int k = 0; k <= d; ++k)
+        t->prof_pairs_level[k < A2A_PROF_MAX_LEVELS ? k : A2A_PROF_MAX_LEVELS - 1] += (int64_t)r.lanes_per_node[k];
     for (auto& x : r.lanes_per_node) x /= (double)gv.G * (double)t->N;
   } catch (const std::bad_alloc&) {
     return A2A_ERR_NO_MEMORY;
@@ -309,7 +319,7 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   const unsigned grid = grid_for(gv.SB, L.nb64, r.inflight);  // thread-per-node kernels
   const unsigned gridw = grid_for(gv.G, L.bpb, r.inflight);   // wave-per-node kernels
   for (int l = 1; l <= depth; ++l) {
-    ProfScope ps(t, PROF_FWD, r.st);
+    ProfScope ps(t, r.sparse(l) ? PROF_FWD_PAIRS : PROF_FWD, r.st, l);
     const bool count = t->prof_mode == 2;
     if (r.sparse(l)) {
       if (count)
@@ -324,6 +334,18 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     }
   }
   HIP_TRY(hipGetLastError());
+  if (t->prof_mode == 2) {  // shortest-path links into each level, for the roofline accounting
+    try {
+      std::vector<long long> dg((size_t)gv.G * L.Lcap);
+      HIP_TRY(hipMemcpyAsync(dg.data(), gv.dag, dg.size() * 8, hipMemcpyDeviceToHost, r.st));
+      HIP_TRY(hipStreamSynchronize(r.st));
+      for (int g = 0; g < gv.G; ++g)
+        for (int l = 0; l <= depth; ++l)
+          t->prof_dag_level[l < A2A_PROF_MAX_LEVELS ? l : A2A_PROF_MAX_LEVELS - 1] += dg[(size_t)g * L.Lcap + l];
+    } catch (const std::bad_alloc&) {
+      return A2A_ERR_NO_MEMORY;
+    }
+  }
   return A2A_OK;
 }
 
@@ -494,7 +516,7 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
     if (rc != A2A_OK) return rc;
   }
   k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), nullptr, (long long*)unreachable,
-                             (long long*)flags, t->prof_mode ? (long long*)t->d_small : nullptr);
+                             (long long*)flags);
   HIP_TRY(hipGetLastError());
   t->prof_calls++;
   return A2A_OK;
@@ -535,12 +557,18 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
       const unsigned grid = grid_for(gv.SB, L.nb64, r.inflight);
       for (int l = depth; l >= 0; --l) {
-        ProfScope ps(t, PROF_BWD, st);
         if (l == depth || (r.sparse(l) && r.sparse(l + 1))) {
           // few sources here and one level down: coef = 1/sigma, then the pairs one by one
-          k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
-          if (l < depth) k_bwd_pairs<<<grid, kBfsBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+          {
+            ProfScope ps(t, PROF_BWD_INIT, st, l);
+            k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
+          }
+          if (l < depth) {
+            ProfScope ps(t, PROF_BWD_PAIRS, st, l);
+            k_bwd_pairs<<<grid, kBfsBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+          }
         } else {
+          ProfScope ps(t, PROF_BWD, st, l);
           k_bwd_level<<<grid_for(gv.G, L.bpb, r.inflight), kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
         }
       }
@@ -552,7 +580,7 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (rc != A2A_OK) return rc;
   }
   k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), (long long*)dist_sum_total,
-                             nullptr, (long long*)flags, t->prof_mode ? (long long*)t->d_small : nullptr);
+                             nullptr, (long long*)flags);
   HIP_TRY(hipGetLastError());
   t->prof_calls++;
   return A2A_OK;
@@ -599,7 +627,8 @@ int a2a_profile_enable(a2a_topo* t, int mode) {
   t->prof_depth = 0;
   t->prof_groups = 0;
   t->prof_mode = mode;
-  HIP_TRY(hipMemset(t->d_small + 8, 0, 8 * sizeof(int64_t)));
+  std::memset(t->prof_pairs_level, 0, sizeof(t->prof_pairs_level));
+  std::memset(t->prof_dag_level, 0, sizeof(t->prof_dag_level));
   return A2A_OK;
 }
 
@@ -607,17 +636,21 @@ int a2a_profile_read(a2a_topo* t, a2a_profile* out) {
   if (!t || !out) return A2A_ERR_INVALID_ARG;
   std::memset(out, 0, sizeof(*out));
   HIP_TRY(hipDeviceSynchronize());
-  const bool dump = std::getenv("A2A_PROF_DUMP") != nullptr;
   for (auto& rec : t->prof_recs) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, rec.beg, rec.end) == hipSuccess && rec.cls >= 0 && rec.cls < PROF_CLASSES) {
       out->ms[rec.cls] += ms;
       out->launches[rec.cls] += 1;
-      if (dump) fprintf(stderr, "a2a_prof cls %d ms %.3f\n", rec.cls, ms);
+      const int l = rec.level < A2A_PROF_MAX_LEVELS ? rec.level : A2A_PROF_MAX_LEVELS - 1;
+      out->ms_level[rec.cls][l] += ms;
     }
   }
   int64_t dag = 0;
-  HIP_TRY(hipMemcpy(&dag, t->d_small + 8, sizeof(dag), hipMemcpyDeviceToHost));
+  for (int l = 0; l < A2A_PROF_MAX_LEVELS; ++l) {
+    out->pairs_level[l] = t->prof_pairs_level[l];
+    out->dag_level[l] = t->prof_dag_level[l];
+    dag += t->prof_dag_level[l];
+  }
   out->dag_links = dag;
   out->calls = t->prof_calls;
   out->depth = t->prof_depth;
