@@ -174,10 +174,10 @@ def main():
         cores = min(os.cpu_count() or 1, 16)
         sample = args.cpu_sources
         if sample is None:
-            # probe 4 sources per thread, then size the sample for about 12 s
-            p = min(N, 4 * cores)
+            # probe 32 sources per thread, then size the sample for about 15 s
+            p = min(N, 32 * cores)
             tp = time.perf_counter(); oracle.run(rp, col, 0, p, threads=cores); tp = time.perf_counter() - tp
-            sample = int(max(p, min(N, p * 12.0 / max(tp, 1e-4))))
+            sample = int(max(p, min(N, p * 15.0 / max(tp, 1e-4))))
         tc = time.perf_counter()
         res = oracle.run(rp, col, 0, sample, threads=cores)
         tc = time.perf_counter() - tc
