@@ -429,11 +429,13 @@ __device__ __forceinline__ int gather8(const double* __restrict__ rows, const Ti
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const uint64_t mk = readlane64(tile.mask, 8 * i + j);
-    const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)tile.off, 8 * i + j);
     m[j] = mk & want;
-    pairs += __popcll(m[j]);
     x[j] = 0.0;
-    if (lane_in(m[j])) x[j] = entry(rows, of + rank_in(mk));
+    if (m[j] != 0) {  // uniform: skip links that carry nothing for this node
+      const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)tile.off, 8 * i + j);
+      pairs += __popcll(m[j]);
+      if (lane_in(m[j])) x[j] = entry(rows, of + rank_in(mk));
+    }
   }
   return pairs;
 }
