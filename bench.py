@@ -150,7 +150,9 @@ def main():
             per_kernel[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps,
                                 "avg_launch_ms": ms / n, "alg_GB_per_step": alg[k] / 1e9,
                                 "alg_GBps": alg[k] / (ms / steps * 1e-3) / 1e9 if ms > 0 else None,
-                                "traffic_bytes_per_launch": read_traffic(name)}
+                                "traffic_bytes_per_launch": read_traffic(name),
+                                "ms_by_level": {str(l): round(x / steps, 3)
+                                                for l, x in enumerate(prof[k]["ms_level"]) if x > 0}}
     dom = max(KERNEL_NAME, key=lambda k: prof[k]["ms"])
     kname = KERNEL_NAME[dom]
     n_l = prof[dom]["launches"]

@@ -37,6 +37,8 @@ SMALL.update({
     "two_components": gen.csr_from_rows([[1], [0], [3], [4], [2]]),
     "no_links": gen.csr_from_rows([[], [], []]),
     "chain_2pow54": gen.csr_from_rows([[i + 1, i + 1] for i in range(54)] + [[]]),
+    # path counts from node 0 are tiny, from node 1 they reach 2^30
+    "late_blowup": gen.csr_from_rows([[]] + [[i + 1, i + 1] for i in range(1, 31)] + [[]]),
 })
 
 
