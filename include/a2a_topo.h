@@ -153,6 +153,25 @@ int a2a_schedule_bound(const a2a_topo* topo, const double* load, int64_t sum_dis
                        double m_bytes, double b_bytes_per_s, a2a_bound* out, void* hip_stream);
 
 /*
+ * Lower bound of Theorem 1 (Sec. 5.4) for any topology with N hosts and out-degree d: a source
+ * reaches at most d^l hosts in l hops, so sum_t D(r,t) >= S_min(N,d), the distance sum of the
+ * arborescence that fills level l with d^l hosts until all N are placed, and by Eq. (lb) the
+ * all-to-all takes at least S_min * m / (d * b).  For N = (d^k - 1)/(d - 1) (full k-layer tree)
+ * S_min = (d^(k+1) (k-1) - d^k k + d) / (d-1)^2.  Host arithmetic only; no device is touched.
+ * Dividing the measured sum of distances (a2a_distances / a2a_link_loads) by N * s_min tells how
+ * close a topology comes to the bound (generalized Kautz graphs approach 1, Sec. 5.4).
+ * Returns A2A_ERR_INVALID_ARG for N < 1, d < 1 (d = 1 with N > 2^31 hosts cannot occur), m <= 0, b <= 0.
+ */
+typedef struct a2a_tree_bound {
+  int64_t s_min;        /* distance sum of the fullest d-ary arborescence on N hosts */
+  int32_t height;       /* its deepest level */
+  int32_t full;         /* 1 if every level is full (closed form of Theorem 1 applies) */
+  double t_lb;          /* s_min * m / (d * b) */
+  double throughput_ub; /* (N-1) * m / t_lb (Sec. 2.2); 0 for N = 1 */
+} a2a_tree_bound;
+int a2a_tree_lower_bound(int32_t N, int32_t d, double m_bytes, double b_bytes_per_s, a2a_tree_bound* out);
+
+/*
  * Optional per-kernel timing, for benchmarks (not part of the paper's method).
  * a2a_profile_enable(topo, mode) clears what was gathered so far and sets the mode:
  *   0  off (default);

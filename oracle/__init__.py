@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     build,
     run,
     bound,
+    tree_sum,
     OracleResult,
     BOUND_FIELDS,
 )

@@ -239,3 +239,23 @@ int a2a_oracle_bound(int32_t N, const int32_t* row_ptr, const double* load, int6
   out[9] = (double)(N - 1) * out[8] * b;
   return 0;
 }
+
+/*
+ * Distance sum of the fullest d-ary arborescence on N nodes (proof of Theorem 1, Sec. 5.4): the
+ * tree whose level l holds d^l nodes until all N are placed.  Written out as the definition on
+ * heap numbering: node 0 is the root, the parent of node i > 0 is (i-1)/d, and the level of a
+ * node is one more than its parent's.  O(N) memory; test sizes only.
+ */
+int64_t a2a_oracle_tree_sum(int32_t N, int32_t d) {
+  if (N < 1 || d < 1) return -1;
+  int32_t* level = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  if (!level) return -1;
+  int64_t sum = 0;
+  level[0] = 0;
+  for (int32_t i = 1; i < N; ++i) {
+    level[i] = level[(i - 1) / d] + 1;
+    sum += level[i];
+  }
+  free(level);
+  return sum;
+}

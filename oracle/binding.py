@@ -47,6 +47,8 @@ def _load():
         lib.a2a_oracle_bound.argtypes = [
             ctypes.c_int32, i32p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_double,
             ctypes.c_double, ctypes.c_void_p]
+        lib.a2a_oracle_tree_sum.restype = ctypes.c_int64
+        lib.a2a_oracle_tree_sum.argtypes = [ctypes.c_int32, ctypes.c_int32]
         _lib = lib
     return _lib
 
@@ -107,3 +109,11 @@ def bound(row_ptr, load, sum_dist: int, m: float = 1.0, b: float = 1.0) -> dict:
     res = dict(zip(BOUND_FIELDS, out.tolist()))
     res["argmax_arc"] = int(res["argmax_arc"])
     return res
+
+
+def tree_sum(N: int, d: int) -> int:
+    """Distance sum of the fullest d-ary arborescence on N nodes (Theorem 1's proof)."""
+    v = int(_load().a2a_oracle_tree_sum(int(N), int(d)))
+    if v < 0:
+        raise ValueError("a2a_oracle_tree_sum rejected its arguments")
+    return v

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     Profile,
     PROF_KERNELS,
     Topology,
+    TreeBound,
+    tree_lower_bound,
     build_library,
     library_path,
     load_library,

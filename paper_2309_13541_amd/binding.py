@@ -38,7 +38,7 @@ FLAG_UNREACHABLE = 0x2
 EXPORTED_SYMBOLS = (
     "a2a_topo_create", "a2a_topo_destroy", "a2a_topo_info", "a2a_workspace_bytes",
     "a2a_distances", "a2a_link_loads", "a2a_schedule_bound", "a2a_status_string",
-    "a2a_profile_enable", "a2a_profile_read",
+    "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound",
 )
 
 PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_pairs", "bwd_rows", "bwd_init", "bwd_pairs",
@@ -69,6 +69,12 @@ class Bound(ctypes.Structure):
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class TreeBound(ctypes.Structure):
+    """Mirror of ``a2a_tree_bound``."""
+    _fields_ = [("s_min", ctypes.c_int64), ("height", ctypes.c_int32), ("full", ctypes.c_int32),
+                ("t_lb", ctypes.c_double), ("throughput_ub", ctypes.c_double)]
 
 
 class Profile(ctypes.Structure):
@@ -141,6 +147,8 @@ def load_library():
     lib.a2a_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.a2a_profile_read.restype = ctypes.c_int
     lib.a2a_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
+    lib.a2a_tree_lower_bound.restype = ctypes.c_int
+    lib.a2a_tree_lower_bound.argtypes = [i32, i32, ctypes.c_double, ctypes.c_double, ctypes.POINTER(TreeBound)]
     lib.a2a_status_string.restype = ctypes.c_char_p
     lib.a2a_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -149,6 +157,14 @@ def load_library():
 
 def status_string(status: int) -> str:
     return load_library().a2a_status_string(int(status)).decode()
+
+
+def tree_lower_bound(N: int, d: int, m_bytes: float = 1.0, b_bytes_per_s: float = 1.0) -> TreeBound:
+    """a2a_tree_lower_bound: Theorem 1's bound for any N-host, degree-d topology (host arithmetic)."""
+    out = TreeBound()
+    _check(load_library().a2a_tree_lower_bound(int(N), int(d), float(m_bytes), float(b_bytes_per_s),
+                                               ctypes.byref(out)), "a2a_tree_lower_bound")
+    return out
 
 
 def _check(status: int, where: str, allow=()):

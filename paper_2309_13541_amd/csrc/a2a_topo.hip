@@ -190,12 +190,6 @@ inline unsigned grid_for(int G, int blocks_per_batch, int inflight = kXcd) {
   return (unsigned)((G + inflight - 1) / inflight * inflight * blocks_per_batch);
 }
 
-inline int env_inflight() {
-  const char* e = std::getenv("A2A_INFLIGHT");
-  const int v = e ? std::atoi(e) : kXcd;
-  return v >= 1 && v <= 64 ? v : kXcd;
-}
-
 // Eccentricity of node 0 over the given CSR by queue BFS; -1 if some node is not reached.
 int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
   std::vector<int32_t> d((size_t)N, -1), q((size_t)N);
@@ -226,7 +220,7 @@ struct Run {
   char* ws;
   hipStream_t st;
   int src_begin, src_count;
-  int inflight = env_inflight();
+  int inflight = kXcd;  // batches in flight = XCDs: one batch's node blocks per XCD at a time
   mutable std::vector<double> lanes_per_node;  // per level of the current group: pairs / (G*N)
   bool sparse(int level) const {
     return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kSparseLanes;
@@ -614,6 +608,28 @@ int a2a_schedule_bound(const a2a_topo* t, const double* load, int64_t sum_dist, 
   out->flow_value = 1.0 / lmax;
   out->throughput_upper = (double)(t->N - 1) * out->flow_value * b;
   return (flags & A2A_FLAG_UNREACHABLE) ? A2A_ERR_DISCONNECTED : A2A_OK;
+}
+
+int a2a_tree_lower_bound(int32_t N, int32_t d, double m_bytes, double b_bytes_per_s, a2a_tree_bound* out) {
+  if (!out || N < 1 || d < 1 || !(m_bytes > 0.0) || !(b_bytes_per_s > 0.0)) return A2A_ERR_INVALID_ARG;
+  int64_t left = (int64_t)N - 1, width = 1, sum = 0;
+  int32_t level = 0;
+  bool full = true;
+  while (left > 0) {
+    ++level;
+    // d^level hosts fit on this level; stop multiplying once it exceeds what is left
+    width = width > left / d ? left + 1 : width * d;
+    const int64_t take = width < left ? width : left;
+    full = take == width;
+    sum += take * level;
+    left -= take;
+  }
+  out->s_min = sum;
+  out->height = level;
+  out->full = full ? 1 : 0;
+  out->t_lb = (double)sum * m_bytes / ((double)d * b_bytes_per_s);
+  out->throughput_ub = N > 1 ? (double)(N - 1) * m_bytes / out->t_lb : 0.0;
+  return A2A_OK;
 }
 
 int a2a_profile_enable(a2a_topo* t, int mode) {

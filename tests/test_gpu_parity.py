@@ -211,3 +211,77 @@ def test_error_paths_on_device(a2a):
     b, st = t2.schedule_bound(topo_load_tensor(l2), d2, f2, allow_disconnected=True)
     assert st == a2a.ERR_DISCONNECTED and b.max_load == 3.0
     topo.close(); t2.close()
+
+
+def test_kautz_approaches_the_tree_bound(a2a, oracle):
+    """Sec. 5.4: generalized Kautz graphs come close to the lower bound of Theorem 1, the ratio
+    approaching 1 for large N; a 2D torus of the same degree falls behind as N grows.  Distance
+    sums from the device (no dist matrix, no path counts), bound from a2a_tree_lower_bound."""
+    import torch
+
+    def ratio(csr, d):
+        rp, col = csr
+        topo = a2a.Topology(rp, col)
+        N = topo.N
+        ws = topo.alloc_workspace(N, a2a.WS_DISTANCES)
+        dsum = torch.zeros(N, dtype=torch.int64, device="cuda")
+        unr = torch.zeros(1, dtype=torch.int64, device="cuda")
+        topo.distances(0, N, dist_sum=dsum, unreachable=unr, workspace=ws)
+        torch.cuda.synchronize()
+        got = dsum.cpu().numpy()
+        o = oracle.run(rp, col, threads=16, want_load=False)
+        assert np.array_equal(got, o.dist_sum) and int(unr.item()) == 0
+        smin = a2a.tree_lower_bound(N, d).s_min
+        assert smin == oracle.tree_sum(N, d)
+        assert got.min() >= smin  # every source obeys the bound
+        topo.close()
+        return float(got.sum()) / (N * smin)
+
+    kautz = {N: ratio(gen.imase_itoh(N, 4), 4) for N in (27, 64, 256, 1024, 4096, 16384)}
+    print("sum D / (N * S_min), Imase-Itoh d=4:", kautz, flush=True)
+    assert all(r >= 1.0 for r in kautz.values())
+    assert kautz[16384] < kautz[4096] < kautz[1024] < kautz[256] < kautz[64] < 1.01
+    assert kautz[16384] < 1.004
+    torus = {k * k: ratio(gen.torus([k, k]), 4) for k in (8, 16, 32)}
+    print("2D torus:", torus, flush=True)
+    assert torus[64] < torus[256] < torus[1024] and torus[1024] > 3.0
+
+
+def test_disabled_links_and_hosts(a2a, oracle):
+    """Degree-irregular topologies made by disabling random links (Sec. 5.3, the N=81, d=8
+    generalized Kautz experiment) and by puncturing a torus (Sec. 5.2): parity with the oracle,
+    and a disconnected outcome is reported, not hidden."""
+    rng = np.random.default_rng(20230913)
+    base = gen.imase_itoh(81, 8)
+    E = len(base[1])
+    for n_off in (3, 20, 80, 200):
+        rp, col = gen.remove_arcs(base, rng.choice(E, size=n_off, replace=False))
+        print(f"case kautz_81_8 minus {n_off} links", flush=True)
+        o = oracle.run(rp, col, want_dist=True, want_sigma=True)
+        topo = a2a.Topology(rp, col)
+        dist, sigma, dsum, unr, flags = run_distances(topo)
+        assert np.array_equal(dist, o.dist) and np.array_equal(dsum, o.dist_sum)
+        assert_sigma_equal(sigma, o.sigma)
+        assert unr == o.unreachable and flags == o.flags
+        load, dtot, lflags = run_link_loads(topo)
+        assert_loads_close(load, o.load)
+        b, st = topo.schedule_bound(topo_load_tensor(load), dtot, lflags, allow_disconnected=True)
+        assert (st == a2a.ERR_DISCONNECTED) == (o.unreachable > 0)
+        ob = oracle.bound(rp, o.load, int(o.dist_sum.sum()))
+        assert b.max_load == pytest.approx(ob["max_load"], rel=1e-9)
+        if o.unreachable == 0:  # the capacity bound with the true link count still holds
+            assert b.t_sched >= b.t_lb_links * (1 - 1e-12)
+        topo.close()
+    torus = gen.torus([3, 3, 3])
+    for kind in ("links", "hosts"):
+        for trial in range(3):
+            if kind == "links":
+                csr = gen.remove_arcs(torus, rng.choice(162, size=3, replace=False))
+            else:
+                csr = gen.remove_nodes(torus, rng.choice(27, size=3, replace=False))
+            o = oracle.run(*csr)
+            topo = a2a.Topology(*csr)
+            load, dtot, lflags = run_link_loads(topo)
+            assert dtot == int(o.dist_sum.sum()) and lflags == o.flags
+            assert_loads_close(load, o.load)
+            topo.close()
