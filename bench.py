@@ -21,8 +21,8 @@ HBM_PEAK_GBPS = 8000.0
 
 
 KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd_level",
-               "fwd_pairs": "k_fwd_pairs", "bwd_rows": "k_bwd_level", "bwd_init": "k_bwd_init_level",
-               "bwd_pairs": "k_bwd_pairs", "reduce": "k_reduce_part"}
+               "fwd_few": "k_fwd_few", "bwd_rows": "k_bwd_level", "bwd_init": "k_bwd_init_level",
+               "bwd_few": "k_bwd_few", "reduce": "k_reduce_part"}
 
 
 def algorithmic_bytes(prof, dag_level, nb, E, steps):
@@ -46,7 +46,7 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
     for l in range(L):
         if ran["bfs"][l]:
             out["bfs"] += 1 * pairs[l]
-        for k in ("fwd_rows", "fwd_pairs"):
+        for k in ("fwd_rows", "fwd_few"):
             if ran[k][l]:
                 out[k] += (1 + 8) * pairs[l] + 8 * dag_in[l]
         part = 8.0 * nb * E * dag_out[l] / dag_total
@@ -54,8 +54,9 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
             out["bwd_rows"] += (8 + 8) * pairs[l] + 8 * dag_out[l] + part
         if ran["bwd_init"][l]:
             out["bwd_init"] += (8 + 8) * pairs[l]
-        if ran["bwd_pairs"][l]:
-            out["bwd_pairs"] += 8 * dag_out[l] + part
+        if ran["bwd_few"][l]:  # after a sweep the level's own entries are charged to the sweep
+            own = 0 if ran["bwd_init"][l] else (8 + 8) * pairs[l]
+            out["bwd_few"] += own + 8 * dag_out[l] + part
     out["reduce"] = 8.0 * nb * E
     return out
 

@@ -41,7 +41,7 @@ EXPORTED_SYMBOLS = (
     "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound",
 )
 
-PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_pairs", "bwd_rows", "bwd_init", "bwd_pairs",
+PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_few", "bwd_rows", "bwd_init", "bwd_few",
                 "reduce", "extract")
 PROF_MAX_LEVELS = 64
 

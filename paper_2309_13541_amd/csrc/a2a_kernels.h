@@ -113,10 +113,11 @@ __device__ __forceinline__ double xor_lanes(double x) {
   return b.d;
 }
 
-// Eight 64-lane sums at once.  x[i] is lane-local; on return every lane l holds the sum over
-// all 64 lanes of x[l & 7].  Halving the value set at each of the first three exchange steps
-// costs 4+2+1+3 exchanges instead of 8*6, in a fixed order (so results are reproducible).
-__device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
+// Eight sums over groups of eight lanes at once.  x[i] is lane-local; on return lane l holds the
+// sum of x[l & 7] over the eight lanes 8*(l>>3) .. 8*(l>>3)+7.  Halving the value set at each
+// exchange step costs 4+2+1 exchanges instead of 8*3, in a fixed order (so results are
+// reproducible).
+__device__ __forceinline__ double group_sum8(const double (&x)[8], int lane) {
   const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
   double y[4], z[2];
 #pragma unroll
@@ -133,7 +134,12 @@ __device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
   }
   const double keep = b2 ? z[1] : z[0];
   const double send = b2 ? z[0] : z[1];
-  double w = keep + xor_lanes<4>(send);
+  return keep + xor_lanes<4>(send);  // lane l: sum of x[l & 7] over the eight lanes of its group
+}
+
+// The same over the whole wave: every lane l gets the sum over all 64 lanes of x[l & 7].
+__device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
+  double w = group_sum8(x, lane);
   w += xor_lanes<8>(w);
   w += xor_lanes<16>(w);
   w += xor_lanes<32>(w);
@@ -210,9 +216,7 @@ constexpr int kBfsWaves = kBfsBlock / kWave;
 struct GroupView {
   uint64_t* bm;       // [SB][Lcap][Npad][kSub] BFS level masks L_l[v]
   uint64_t* seen;     // [SB][Npad][kSub]
-  NodeIdx* idx;       // [SB][Lcap][Npad][kSub] mask + row offset, for the thread-per-node kernels
-  NodeIdx* idxb;      // [G][Lcap][Npad]        the same per batch, for the wave-per-node kernels
-                      //                        (both nullptr: distances only)
+  NodeIdx* idxb;      // [G][Lcap][Npad]  mask + row offset per batch (nullptr: distances only)
   double* dat;        // [G][Npad*64]  level-compact sigma (nullptr: distances only)
   double* coef;       // [G][Npad*64]  level-compact coef (link loads only)
   int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level;
@@ -227,15 +231,6 @@ struct GroupView {
 
 __device__ __forceinline__ size_t bm_at(const GroupView& gv, int sb, int level, int v, int k) {
   return ((((size_t)sb * gv.Lcap + level) * gv.Npad) + v) * kSub + k;
-}
-
-// idx of batch sb*kSub+k at a level: element v is p[v * kSub].  The entries of one node for the
-// kSub batches of a super-batch share a 128-byte line: the kSub lanes that look at the same
-// node for different batches share the memory request.  The wave-per-node kernels, which work
-// on one batch per XCD at a time, use the per-batch copy idxb instead: a super-batch's level
-// (kSub times larger) would not stay in that XCD's L2.
-__device__ __forceinline__ NodeIdx* idx_level(const GroupView& gv, int sb, int level, int k) {
-  return gv.idx + bm_at(gv, sb, level, 0, k);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -331,7 +326,7 @@ __global__ void __launch_bounds__(kWave) k_scan_blocks(GroupView gv, int depth) 
   }
 }
 
-// Index arrays from the BFS masks: idx[sb][l][v][k] = { L_l[v], first entry of the row }.
+// Index array from the BFS masks: idxb[g][l][v] = { L_l[v], first entry of the row }.
 // Thread (node, k) as in the BFS; the row offsets are an exclusive prefix over nodes for each
 // batch k (three shuffle steps across the 8 nodes of a wave, then across the 8 waves via LDS).
 __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int depth) {
@@ -365,8 +360,7 @@ __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int d
       n.off = (uint32_t)(base + x - c);
       __syncthreads();
     }
-    gv.idx[bm_at(gv, sb, l, v, k)] = n;
-    // per-batch copy: wave w writes the 64 consecutive entries of batch sb*kSub+w
+    // transpose through LDS: wave w writes the 64 consecutive entries of batch sb*kSub+w
     s_n[k][t / kSub] = n;
     __syncthreads();
     const int gw = sb * kSub + wid;
@@ -664,63 +658,330 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   }
 }
 
-// --- sparsely populated levels: one thread per (batch, node) -------------------------------
+// --- levels with few sources per node: one lane per (node, link) ---------------------------
 //
-// When a level holds only a few sources per node, a wave per node leaves most lanes idle and
-// pays the full per-node instruction cost for a handful of values.  These kernels give every
-// lane its own node and walk the (source, link) pairs one by one; sums are taken in a fixed
-// serial order (links in CSR order, sources in ascending order).
+// With a handful of sources per node, a lane per source leaves most of the wave idle and still
+// pays the per-link instruction cost.  These kernels keep the index tile's layout for the
+// arithmetic as well: lane 8i+j owns link j of node i and walks the node's sources in ascending
+// order, the eight lanes of a node in step.  Per source the lane reads its link's entry (if the
+// link carries that source), the eight lanes add up in a fixed order, and lane j = 0 writes the
+// node's entry; the node's own row is compact, so its k-th source is simply entry k of the row.
+// The entries of the next source are requested before the current ones are used.
 
 __device__ __forceinline__ uint32_t below(uint64_t mask, int s) {
   return (uint32_t)__popcll(mask & ((1ull << s) - 1ull));
 }
 
-// Forward, sparse level: sigma(s,v) accumulated pair by pair into the node's own entries.
-template <bool kCountDag>
-__global__ void __launch_bounds__(kBfsBlock)
-k_fwd_pairs(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
-            int level, long long* __restrict__ misc) {
-  int sb, nblk;
-  if (!map_block(gv.SB, gv.nb64, gv.inflight, sb, nblk)) return;
-  const int v = nblk * kBfsNodes + (int)threadIdx.x / kSub, k = (int)threadIdx.x % kSub;
-  const int g = sb * kSub + k;
-  const NodeIdx* __restrict__ cur = idx_level(gv, sb, level, k);
-  const NodeIdx* __restrict__ prev = idx_level(gv, sb, level - 1, k);
-  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;  // not touched if g >= G: no masks
-  const NodeIdx me = load_idx(cur + (size_t)v * kSub);
-  int dag = 0;
-  bool inexact = false;
-  if (me.mask != 0) {
-    uint64_t started = 0;  // sources whose entry has received its first term
-    const int p1 = in_ptr[v + 1];
-    for (int p = in_ptr[v]; p < p1; ++p) {
-      const NodeIdx ix = load_idx(prev + (size_t)in_col[p] * kSub);
-      uint64_t m = ix.mask & me.mask;
-      if (kCountDag) dag += __popcll(m);
-      while (m) {
-        const int s = __builtin_ctzll(m);
-        m &= m - 1;
-        const double val = dat[ix.off + below(ix.mask, s)];
-        double* mine = dat + me.off + below(me.mask, s);
-        const double sum = ((started >> s) & 1ull) ? *mine + val : val;
-        *mine = sum;
-        inexact |= sum >= kTwo53;
-        started |= 1ull << s;
-      }
+// Value of lane kSrc of this lane's group of eight lanes.
+template <int kSrc>
+__device__ __forceinline__ double bcast8(double x) {
+  union {
+    double d;
+    int i[2];
+  } a, b;
+  a.d = x;  // ds_swizzle, bit mode: lane = (lane & 0x18) | kSrc within each half of the wave
+  b.i[0] = __builtin_amdgcn_ds_swizzle(a.i[0], 0x18 | (kSrc << 5));
+  b.i[1] = __builtin_amdgcn_ds_swizzle(a.i[1], 0x18 | (kSrc << 5));
+  return b.d;
+}
+
+// The next (up to) eight sources of `rest`, lowest first: x[k] = the entry of the k-th of them in
+// the link's row (mk, ofk), 0 if the link does not carry it or there is no k-th source.  All
+// requests are issued before any value is used.
+__device__ __forceinline__ void few_fetch8(const double* __restrict__ rows, uint64_t mk, uint32_t ofk, uint64_t& rest,
+                                           double (&x)[8]) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    x[k] = 0.0;
+    if (rest != 0) {
+      const int s = __builtin_ctzll(rest);
+      rest &= rest - 1;
+      if ((mk >> s) & 1ull) x[k] = entry(rows, ofk + below(mk, s));
     }
   }
+}
+
+// sigma of the node's sources from one tile of in-links (mu, ofu: the node's own mask and row).
+// Lane j of the node ends up with the sum for the node's j-th source and writes that entry.
+__device__ __forceinline__ bool few_fwd(double* __restrict__ dat, const Tile& tl, uint64_t mu, uint32_t ofu, bool add,
+                                        int lane) {
+  uint64_t rest = mu;
+  uint32_t e = ofu + (uint32_t)(lane & 7);
+  int left = __popcll(mu) - (lane & 7);  // > 0: this lane owns a source of the current eight
+  bool big = false;
+  while (__ballot(rest != 0) != 0) {
+    double x[8];
+    few_fetch8(dat, tl.mask, tl.off, rest, x);
+    double a = group_sum8(x, lane);
+    if (left > 0 && !(add && a == 0.0)) {
+      if (add) a += entry(dat, e);
+      entry(dat, e) = a;
+      big |= a >= kTwo53;
+    }
+    e += 8;
+    left -= 8;
+  }
+  return big;
+}
+
+// coef of the node's sources and this lane's link load from one tile of out-links.
+__device__ __forceinline__ double few_bwd(const double* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
+                                          uint64_t mu, uint32_t ofu, bool add, int lane) {
+  uint64_t rest = mu;
+  uint32_t e = ofu + (uint32_t)(lane & 7);
+  int left = __popcll(mu) - (lane & 7);
+  double acc = 0.0;
+  while (__ballot(rest != 0) != 0) {
+    double x[8];
+    few_fetch8(cf, tl.mask, tl.off, rest, x);
+    double sg = 1.0;  // lane j: sigma of the node's j-th source of these eight
+    if (left > 0) sg = entry(dat, e);
+    acc = __builtin_fma(bcast8<0>(sg), x[0], acc);
+    acc = __builtin_fma(bcast8<1>(sg), x[1], acc);
+    acc = __builtin_fma(bcast8<2>(sg), x[2], acc);
+    acc = __builtin_fma(bcast8<3>(sg), x[3], acc);
+    acc = __builtin_fma(bcast8<4>(sg), x[4], acc);
+    acc = __builtin_fma(bcast8<5>(sg), x[5], acc);
+    acc = __builtin_fma(bcast8<6>(sg), x[6], acc);
+    acc = __builtin_fma(bcast8<7>(sg), x[7], acc);
+    double a = group_sum8(x, lane);
+    if (left > 0 && !(add && a == 0.0)) {
+      a += add ? entry(cf, e) : recip(sg);
+      entry(cf, e) = a;
+    }
+    e += 8;
+    left -= 8;
+  }
+  return acc;
+}
+
+// --- the same levels with a lane per (node, source) ---------------------------------------
+//
+// Second lane layout for the same tile: lane 8i+k owns the k-th source of node i (eight sources
+// per round) and walks the node's links, all lanes on link j at the same time.  The lanes of a
+// node then read the same row, so their requests share its memory lines, and the sum over the
+// links is lane-local; only the link loads need one exchange per tile.  Costs the same
+// whether the node has one source or eight, so it pays from a few sources per node upwards.
+
+template <int kSrc>
+__device__ __forceinline__ uint32_t bcast8(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x18 | (kSrc << 5));
+}
+template <int kSrc>
+__device__ __forceinline__ uint64_t bcast8(uint64_t x) {
+  return ((uint64_t)bcast8<kSrc>((uint32_t)(x >> 32)) << 32) | bcast8<kSrc>((uint32_t)x);
+}
+
+// OR over the eight lanes of a node; every one of them gets the result.
+__device__ __forceinline__ uint32_t or_links8(uint32_t x) {
+  x |= (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x141, 0xF, 0xF, true);  // row_half_mirror
+  x |= (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+  x |= (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+  return x;
+}
+__device__ __forceinline__ uint64_t or_links8(uint64_t x) {
+  return ((uint64_t)or_links8((uint32_t)(x >> 32)) << 32) | or_links8((uint32_t)x);
+}
+
+// Removes the next (up to) eight sources from `rest`; returns the k-th of them, -1 if none.
+__device__ __forceinline__ int slot_take8(uint64_t& rest, int k) {
+  int mine = -1;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    if (rest != 0) {
+      const int s = __builtin_ctzll(rest);
+      rest &= rest - 1;
+      if (t == k) mine = s;
+    }
+  }
+  return mine;
+}
+
+// x[j] = entry of source s in the row of link j of this lane's node (0 if not carried).
+template <int kJ>
+__device__ __forceinline__ double slot_fetch(const double* __restrict__ rows, const Tile& tl, int s) {
+  const uint64_t mk = bcast8<kJ>(tl.mask);
+  const uint32_t ofk = bcast8<kJ>(tl.off);
+  double x = 0.0;
+  if (s >= 0 && ((mk >> s) & 1ull)) x = entry(rows, ofk + below(mk, s));
+  return x;
+}
+__device__ __forceinline__ void slot_fetch8(const double* __restrict__ rows, const Tile& tl, int s, double (&x)[8]) {
+  x[0] = slot_fetch<0>(rows, tl, s);
+  x[1] = slot_fetch<1>(rows, tl, s);
+  x[2] = slot_fetch<2>(rows, tl, s);
+  x[3] = slot_fetch<3>(rows, tl, s);
+  x[4] = slot_fetch<4>(rows, tl, s);
+  x[5] = slot_fetch<5>(rows, tl, s);
+  x[6] = slot_fetch<6>(rows, tl, s);
+  x[7] = slot_fetch<7>(rows, tl, s);
+}
+
+__device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, const Tile& tl, uint64_t mu, uint32_t ofu, bool add,
+                                         int lane) {
+  uint64_t rest = mu;
+  uint32_t e = ofu + (uint32_t)(lane & 7);
+  bool big = false;
+  while (__ballot(rest != 0) != 0) {
+    const int s = slot_take8(rest, lane & 7);
+    double x[8];
+    slot_fetch8(dat, tl, s, x);
+    double a = 0.0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a += x[j];
+    if (s >= 0 && !(add && a == 0.0)) {
+      if (add) a += entry(dat, e);
+      entry(dat, e) = a;
+      big |= a >= kTwo53;
+    }
+    e += 8;
+  }
+  return big;
+}
+
+// Returns, in lane 8i+j, the load of link j of node i from this tile.  kUnion: the node's row
+// already holds 1/sigma and only the sources that some link of the tile carries are visited
+// (a well-filled level whose successors are sparse); their entries are then found by rank.
+template <bool kUnion>
+__device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
+                                           uint64_t mu, uint32_t ofu, bool add, int lane) {
+  uint64_t rest = kUnion ? or_links8(tl.mask & mu) : mu;
+  uint32_t e = ofu + (uint32_t)(lane & 7);
+  double p[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = 0.0;
+  while (__ballot(rest != 0) != 0) {
+    const int s = slot_take8(rest, lane & 7);
+    if (kUnion) e = ofu + (s >= 0 ? below(mu, s) : 0u);
+    double x[8];
+    slot_fetch8(cf, tl, s, x);
+    double sg = 1.0;
+    if (s >= 0) sg = entry(dat, e);
+    double a = 0.0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      a += x[j];
+      p[j] = __builtin_fma(sg, x[j], p[j]);
+    }
+    if (s >= 0 && !((add || kUnion) && a == 0.0)) {
+      a += (add || kUnion) ? entry(cf, e) : recip(sg);
+      entry(cf, e) = a;
+    }
+    if (!kUnion) e += 8;
+  }
+  return group_sum8(p, lane);
+}
+
+template <bool kCountDag, bool kSlots>
+__global__ void __launch_bounds__(kBlock)
+k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
+          long long* __restrict__ misc) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int lane = lane_id();
+  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (v0 >= gv.N) return;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const NodeIdx me = load_idx(cur + v0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
+  if (nodes_active == 0) return;
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (me.mask != 0) {
+    lr.p0 = in_ptr[v0 + lane];
+    lr.p1 = in_ptr[v0 + lane + 1];
+  }
+  bool inexact = false;
+  int dag = 0;
+  int q;
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
+  int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
+#pragma unroll 1
+  for (int c = 0; c < 8; ++c) {
+    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
+    nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+      const int node = 8 * c + (lane >> 3);
+      const uint64_t mu = shfl64(me.mask, node);
+      const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
+      inexact |= kSlots ? slot_fwd(dat, tile, mu, ofu, false, lane) : few_fwd(dat, tile, mu, ofu, false, lane);
+      if (kCountDag) dag += __popcll(tile.mask & mu);
+      // nodes with more than eight in-links: add the rest to the stored entries
+      const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
+      for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
+        const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
+        inexact |= kSlots ? slot_fwd(dat, extra, mu, ofu, true, lane) : few_fwd(dat, extra, mu, ofu, true, lane);
+        if (kCountDag) dag += __popcll(extra.mask & mu);
+      }
+    }
+    tile = tile_next;
+  }
   if (inexact) misc[0] = 1;
-  if (kCountDag) {  // lanes with the same k sum up: lane k of the wave adds for batch k
-    dag += __shfl_xor(dag, 8, kWave);
-    dag += __shfl_xor(dag, 16, kWave);
-    dag += __shfl_xor(dag, 32, kWave);
-    if (dag != 0 && lane_id() < kSub)
+  if (kCountDag) {
+    dag = wave_sum_int(dag);
+    if (dag != 0 && lane == 0)
       atomicAdd((unsigned long long*)&gv.dag[(size_t)g * gv.Lcap + level], (unsigned long long)dag);
   }
 }
 
-// Backward, start of a level handled pair by pair: coef = 1/sigma for every entry of the level
-// (a flat sweep over the level's slice of the compact arrays).
+template <bool kSlots, bool kUnion>
+__global__ void __launch_bounds__(kBlock)
+k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int lane = lane_id();
+  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (u0 >= gv.N) return;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
+  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const NodeIdx me = load_idx(cur + u0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
+  if (nodes_active == 0) return;
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (me.mask != 0) {
+    lr.p0 = out_ptr[u0 + lane];
+    lr.p1 = out_ptr[u0 + lane + 1];
+  }
+  int q, q_next, q_nn;
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
+  int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
+#pragma unroll 1
+  for (int c = 0; c < 8; ++c) {
+    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+    nb_next = -1;
+    q_nn = -1;
+    if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+      const int node = 8 * c + (lane >> 3);
+      const uint64_t mu = shfl64(me.mask, node);
+      const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
+      const double tot =
+          kSlots ? slot_bwd<kUnion>(dat, cf, tile, mu, ofu, false, lane) : few_bwd(dat, cf, tile, mu, ofu, false, lane);
+      if (q >= 0 && (tile.mask & mu) != 0) pt[q] += tot;
+      // nodes with more than eight out-links: add the rest to the stored coef
+      const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
+      for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
+        int qe;
+        const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
+        const double te =
+            kSlots ? slot_bwd<kUnion>(dat, cf, extra, mu, ofu, true, lane) : few_bwd(dat, cf, extra, mu, ofu, true, lane);
+        if (qe >= 0 && (extra.mask & mu) != 0) pt[qe] += te;
+      }
+    }
+    tile = tile_next;
+    q = q_next;
+    q_next = q_nn;
+  }
+}
+
+// coef = 1/sigma for every entry of a level (a flat sweep over the level's slice of the compact
+// arrays): the deepest level, and levels whose rows k_bwd_few then only adds to.
 __global__ void __launch_bounds__(kBfsBlock) k_bwd_init_level(GroupView gv, int level) {
   int sb, nblk;
   if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
@@ -734,40 +995,6 @@ __global__ void __launch_bounds__(kBfsBlock) k_bwd_init_level(GroupView gv, int 
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64 + base;
   for (long long e = (long long)nblk * kWave + lane_id(); e < cnt; e += (long long)gv.nb64 * kWave)
     cf[e] = recip(dat[e]);
-}
-
-// Backward, sparse successors: for every (source, link) pair with the link's head one level
-// down, coef(s,u) += coef(s,w) and load(u,w) += sigma(s,u) * coef(s,w).
-__global__ void __launch_bounds__(kBfsBlock)
-k_bwd_pairs(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
-            int level) {
-  int sb, nblk;
-  if (!map_block(gv.SB, gv.nb64, gv.inflight, sb, nblk)) return;
-  const int u = nblk * kBfsNodes + (int)threadIdx.x / kSub, k = (int)threadIdx.x % kSub;
-  const int g = sb * kSub + k;
-  const NodeIdx* __restrict__ cur = idx_level(gv, sb, level, k);
-  const NodeIdx* __restrict__ next = idx_level(gv, sb, level + 1, k);
-  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
-  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
-  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
-  const NodeIdx me = load_idx(cur + (size_t)u * kSub);
-  if (me.mask == 0) return;
-  const int p1 = out_ptr[u + 1];
-  for (int p = out_ptr[u]; p < p1; ++p) {
-    const NodeIdx ix = load_idx(next + (size_t)out_col[p] * kSub);
-    uint64_t m = ix.mask & me.mask;
-    if (m == 0) continue;
-    double x = 0.0;
-    while (m) {
-      const int s = __builtin_ctzll(m);
-      m &= m - 1;
-      const double c = cf[ix.off + below(ix.mask, s)];
-      const uint32_t mine = me.off + below(me.mask, s);
-      x += dat[mine] * c;
-      cf[mine] += c;
-    }
-    pt[p] += x;
-  }
 }
 
 // load[a] = (first group ? 0 : load[a]) + part[0][a] + part[1][a] + ... in that order.

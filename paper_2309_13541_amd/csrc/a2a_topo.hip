@@ -11,6 +11,7 @@
 //   sum    load += per-batch loads, in ascending batch order
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -51,8 +52,8 @@ namespace {
 
 enum {
   PROF_INIT = A2A_K_INIT, PROF_BFS = A2A_K_BFS, PROF_OFFSETS = A2A_K_OFFSETS, PROF_FWD = A2A_K_FWD_ROWS,
-  PROF_FWD_PAIRS = A2A_K_FWD_PAIRS, PROF_BWD = A2A_K_BWD_ROWS, PROF_BWD_INIT = A2A_K_BWD_INIT,
-  PROF_BWD_PAIRS = A2A_K_BWD_PAIRS, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
+  PROF_FWD_FEW = A2A_K_FWD_FEW, PROF_BWD = A2A_K_BWD_ROWS, PROF_BWD_INIT = A2A_K_BWD_INIT,
+  PROF_BWD_FEW = A2A_K_BWD_FEW, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
   PROF_CLASSES = A2A_K_COUNT
 };
 
@@ -75,7 +76,6 @@ struct Layout {
   size_t off_bsum = 0;       // int32 [SB*kSub][Lcap][nb64]
   size_t off_seen = 0;       // uint64 [SB][Npad][kSub]
   size_t off_bm = 0;         // uint64 [SB][Lcap][Npad][kSub]
-  size_t off_idx = 0;        // NodeIdx [SB][Lcap][Npad][kSub] (with sigma / loads)
   size_t off_idxb = 0;       // NodeIdx [G][Lcap][Npad]        (with sigma / loads)
   size_t off_dat = 0;        // double [G][Npad*64]  sigma
   size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
@@ -111,7 +111,6 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_bsum = take(SB * kSub * L.Lcap * L.nb64 * 4);
     const size_t o_seen = take(SB * L.Npad * kSub * 8);
     const size_t o_bm = take(SB * L.Lcap * L.Npad * kSub * 8);
-    const size_t o_idx = L.values ? take(SB * L.Lcap * L.Npad * kSub * sizeof(NodeIdx)) : 0;
     const size_t o_idxb = L.values ? take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx)) : 0;
     const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8) : 0;
     const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8) : 0;
@@ -125,7 +124,6 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->off_seen = o_seen;
       out->off_bm = o_bm;
       out->SB = (int)SB;
-      out->off_idx = o_idx;
       out->off_idxb = o_idxb;
       out->off_dat = o_dat;
       out->off_coef = o_coef;
@@ -210,9 +208,14 @@ int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
   return tail == N ? ecc : -1;
 }
 
-// Average number of sources per node below which a level is handled pair by pair (one thread
-// per node) instead of row by row (one wave per node).
-constexpr double kSparseLanes = 8.0;
+// Which kernel flavour a level gets, from the average number of sources per node on it:
+// below kFewLanes the lanes of a wave stand for (node, link) or (node, source) pairs of eight
+// nodes (k_fwd_few / k_bwd_few), from kSlotLanes on in the (node, source) layout; above, one wave
+// per node with a lane per source (k_fwd_level / k_bwd_level).  A well-filled level whose nodes
+// have fewer than kFewLanes sources with a successor is swept with 1/sigma and then visited by
+// k_bwd_few for those sources only.
+constexpr double kFewLanes = 8.0;
+constexpr double kSlotLanes = 2.0;
 
 struct Run {
   const a2a_topo* t;
@@ -222,15 +225,21 @@ struct Run {
   int src_begin, src_count;
   int inflight = kXcd;  // batches in flight = XCDs: one batch's node blocks per XCD at a time
   mutable std::vector<double> lanes_per_node;  // per level of the current group: pairs / (G*N)
-  bool sparse(int level) const {
-    return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kSparseLanes;
+  bool few(int level) const {
+    return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kFewLanes;
+  }
+  bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
+  // Expected number of sources of a node on level l that have a successor on level l+1.
+  double with_successors(int l) const {
+    if (l < 0 || l + 1 >= (int)lanes_per_node.size()) return 0.0;
+    const double deg = (double)t->E / (double)t->N;
+    return lanes_per_node[l] * (1.0 - std::exp(-deg * lanes_per_node[l + 1] / 64.0));
   }
   int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
   GroupView view(int batch0, int G) const {
     GroupView gv;
     gv.bm = (uint64_t*)(ws + L.off_bm);
-    gv.idx = L.values ? (NodeIdx*)(ws + L.off_idx) : nullptr;
     gv.idxb = L.values ? (NodeIdx*)(ws + L.off_idxb) : nullptr;
     gv.seen = (uint64_t*)(ws + L.off_seen);
     gv.dat = L.values ? (double*)(ws + L.off_dat) : nullptr;
@@ -310,22 +319,19 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     if (depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * depth), kWave, 0, r.st>>>(gv, depth);
     k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, depth);
   }
-  const unsigned grid = grid_for(gv.SB, L.nb64, r.inflight);  // thread-per-node kernels
-  const unsigned gridw = grid_for(gv.G, L.bpb, r.inflight);   // wave-per-node kernels
+  const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
-    ProfScope ps(t, r.sparse(l) ? PROF_FWD_PAIRS : PROF_FWD, r.st, l);
+    ProfScope ps(t, r.few(l) ? PROF_FWD_FEW : PROF_FWD, r.st, l);
     const bool count = t->prof_mode == 2;
-    if (r.sparse(l)) {
-      if (count)
-        k_fwd_pairs<true><<<grid, kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
-      else
-        k_fwd_pairs<false><<<grid, kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
-    } else {
-      if (count)
-        k_fwd_level<true><<<gridw, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
-      else
-        k_fwd_level<false><<<gridw, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
-    }
+    auto launch = [&](auto kernel) {
+      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+    };
+    if (!r.few(l))
+      count ? launch(k_fwd_level<true>) : launch(k_fwd_level<false>);
+    else if (r.slots(l))
+      count ? launch(k_fwd_few<true, true>) : launch(k_fwd_few<false, true>);
+    else
+      count ? launch(k_fwd_few<true, false>) : launch(k_fwd_few<false, false>);
   }
   HIP_TRY(hipGetLastError());
   if (t->prof_mode == 2) {  // shortest-path links into each level, for the roofline accounting
@@ -549,22 +555,24 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (rc != A2A_OK) return rc;
     if (t->E > 0) {
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
-      const unsigned grid = grid_for(gv.SB, L.nb64, r.inflight);
+      const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
       for (int l = depth; l >= 0; --l) {
-        if (l == depth || (r.sparse(l) && r.sparse(l + 1))) {
-          // few sources here and one level down: coef = 1/sigma, then the pairs one by one
-          {
-            ProfScope ps(t, PROF_BWD_INIT, st, l);
-            k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
-          }
-          if (l < depth) {
-            ProfScope ps(t, PROF_BWD_PAIRS, st, l);
-            k_bwd_pairs<<<grid, kBfsBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
-          }
-        } else {
-          ProfScope ps(t, PROF_BWD, st, l);
-          k_bwd_level<<<grid_for(gv.G, L.bpb, r.inflight), kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l);
+        const bool sweep = l == depth || (!r.few(l) && r.with_successors(l) < kFewLanes);
+        if (sweep) {
+          ProfScope ps(t, PROF_BWD_INIT, st, l);
+          k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
         }
+        if (l == depth) continue;
+        ProfScope ps(t, sweep || r.few(l) ? PROF_BWD_FEW : PROF_BWD, st, l);
+        auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
+        if (sweep)
+          launch(k_bwd_few<true, true>);
+        else if (!r.few(l))
+          launch(k_bwd_level);
+        else if (r.slots(l))
+          launch(k_bwd_few<true, false>);
+        else
+          launch(k_bwd_few<false, false>);
       }
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(
