@@ -435,7 +435,9 @@ __device__ __forceinline__ int gather8(const double* __restrict__ rows, const Ti
 }
 
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
-__device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, const NodeIdx& me, int node, const double (&x)[8]) {
+// cf (may be null): the backward pass will only add to this level's coef, so 1/sigma goes there now.
+__device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __restrict__ cf, const NodeIdx& me,
+                                           int node, const double (&x)[8]) {
   double a = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) a += x[j];
@@ -443,7 +445,9 @@ __device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, const NodeI
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
   bool big = false;
   if (lane_in(newv)) {
-    entry(dat, of + rank_in(newv)) = a;
+    const uint32_t e = of + rank_in(newv);
+    entry(dat, e) = a;
+    if (cf != nullptr) entry(cf, e) = recip(a);
     big = a >= kTwo53;
   }
   return big;
@@ -452,7 +456,7 @@ __device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, const NodeI
 template <bool kCountDag>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
-            int level, long long* __restrict__ misc) {
+            int level, bool init_coef, long long* __restrict__ misc) {
   int g, nblk;
   if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
@@ -461,6 +465,7 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -486,9 +491,9 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
 #pragma unroll 1
       for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
         pairs += gather8(dat, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
-        inexact |= fwd_finish(dat, me, 8 * c + i, xa);
+        inexact |= fwd_finish(dat, cf, me, 8 * c + i, xa);
         if (i + 2 < 8) pairs += gather8(dat, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
-        inexact |= fwd_finish(dat, me, 8 * c + i + 1, xb);
+        inexact |= fwd_finish(dat, cf, me, 8 * c + i + 1, xb);
       }
       if (kCountDag) dag += pairs;
       // nodes with more than eight in-links: add the rest to the stored entries
@@ -506,9 +511,10 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
           for (int j = 0; j < 8; ++j) a += xa[j];
           const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
           if (lane_in(newv)) {
-            double& e = entry(dat, of + rank_in(newv));
-            a += e;
-            e = a;
+            const uint32_t pos = of + rank_in(newv);
+            a += entry(dat, pos);
+            entry(dat, pos) = a;
+            if (cf != nullptr) entry(cf, pos) = recip(a);
             inexact |= a >= kTwo53;
           }
         }
@@ -703,8 +709,8 @@ __device__ __forceinline__ void few_fetch8(const double* __restrict__ rows, uint
 
 // sigma of the node's sources from one tile of in-links (mu, ofu: the node's own mask and row).
 // Lane j of the node ends up with the sum for the node's j-th source and writes that entry.
-__device__ __forceinline__ bool few_fwd(double* __restrict__ dat, const Tile& tl, uint64_t mu, uint32_t ofu, bool add,
-                                        int lane) {
+__device__ __forceinline__ bool few_fwd(double* __restrict__ dat, double* __restrict__ cf, const Tile& tl, uint64_t mu,
+                                        uint32_t ofu, bool add, int lane) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   int left = __popcll(mu) - (lane & 7);  // > 0: this lane owns a source of the current eight
@@ -716,6 +722,7 @@ __device__ __forceinline__ bool few_fwd(double* __restrict__ dat, const Tile& tl
     if (left > 0 && !(add && a == 0.0)) {
       if (add) a += entry(dat, e);
       entry(dat, e) = a;
+      if (cf != nullptr) entry(cf, e) = recip(a);
       big |= a >= kTwo53;
     }
     e += 8;
@@ -817,8 +824,8 @@ __device__ __forceinline__ void slot_fetch8(const double* __restrict__ rows, con
   x[7] = slot_fetch<7>(rows, tl, s);
 }
 
-__device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, const Tile& tl, uint64_t mu, uint32_t ofu, bool add,
-                                         int lane) {
+__device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, double* __restrict__ cf, const Tile& tl, uint64_t mu,
+                                         uint32_t ofu, bool add, int lane) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   bool big = false;
@@ -832,6 +839,7 @@ __device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, const Tile& t
     if (s >= 0 && !(add && a == 0.0)) {
       if (add) a += entry(dat, e);
       entry(dat, e) = a;
+      if (cf != nullptr) entry(cf, e) = recip(a);
       big |= a >= kTwo53;
     }
     e += 8;
@@ -855,8 +863,13 @@ __device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, doubl
     if (kUnion) e = ofu + (s >= 0 ? below(mu, s) : 0u);
     double x[8];
     slot_fetch8(cf, tl, s, x);
-    double sg = 1.0;
-    if (s >= 0) sg = entry(dat, e);
+    double sg = 1.0, was = 1.0;
+    if (kUnion) {  // the row holds 1/sigma (plus earlier rounds): sigma from there, one read less
+      if (s >= 0) was = entry(cf, e);
+      sg = add ? (s >= 0 ? entry(dat, e) : 1.0) : recip(was);
+    } else if (s >= 0) {
+      sg = entry(dat, e);
+    }
     double a = 0.0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -864,7 +877,7 @@ __device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, doubl
       p[j] = __builtin_fma(sg, x[j], p[j]);
     }
     if (s >= 0 && !((add || kUnion) && a == 0.0)) {
-      a += (add || kUnion) ? entry(cf, e) : recip(sg);
+      a += kUnion ? was : (add ? entry(cf, e) : recip(sg));
       entry(cf, e) = a;
     }
     if (!kUnion) e += 8;
@@ -875,7 +888,7 @@ __device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, doubl
 template <bool kCountDag, bool kSlots>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
-          long long* __restrict__ misc) {
+          bool init_coef, long long* __restrict__ misc) {
   int g, nblk;
   if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
@@ -884,6 +897,7 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -906,13 +920,13 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
-      inexact |= kSlots ? slot_fwd(dat, tile, mu, ofu, false, lane) : few_fwd(dat, tile, mu, ofu, false, lane);
+      inexact |= kSlots ? slot_fwd(dat, cf, tile, mu, ofu, false, lane) : few_fwd(dat, cf, tile, mu, ofu, false, lane);
       if (kCountDag) dag += __popcll(tile.mask & mu);
       // nodes with more than eight in-links: add the rest to the stored entries
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
-        inexact |= kSlots ? slot_fwd(dat, extra, mu, ofu, true, lane) : few_fwd(dat, extra, mu, ofu, true, lane);
+        inexact |= kSlots ? slot_fwd(dat, cf, extra, mu, ofu, true, lane) : few_fwd(dat, cf, extra, mu, ofu, true, lane);
         if (kCountDag) dag += __popcll(extra.mask & mu);
       }
     }
@@ -981,7 +995,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
 }
 
 // coef = 1/sigma for every entry of a level (a flat sweep over the level's slice of the compact
-// arrays): the deepest level, and levels whose rows k_bwd_few then only adds to.
+// arrays): level 0, when the forward pass did not run and could not leave it there.
 __global__ void __launch_bounds__(kBfsBlock) k_bwd_init_level(GroupView gv, int level) {
   int sb, nblk;
   if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;

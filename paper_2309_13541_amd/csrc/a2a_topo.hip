@@ -229,6 +229,10 @@ struct Run {
     return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kFewLanes;
   }
   bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
+  // Backward level that starts from coef = 1/sigma and only visits the sources with a successor.
+  bool coef_from_forward(int level, int depth) const {
+    return level == depth || (!few(level) && with_successors(level) < kFewLanes);
+  }
   // Expected number of sources of a node on level l that have a successor on level l+1.
   double with_successors(int l) const {
     if (l < 0 || l + 1 >= (int)lanes_per_node.size()) return 0.0;
@@ -323,8 +327,10 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   for (int l = 1; l <= depth; ++l) {
     ProfScope ps(t, r.few(l) ? PROF_FWD_FEW : PROF_FWD, r.st, l);
     const bool count = t->prof_mode == 2;
+    // levels that the backward pass only adds to get coef = 1/sigma from the forward pass
+    const bool init_coef = gv.coef != nullptr && r.coef_from_forward(l, depth);
     auto launch = [&](auto kernel) {
-      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
+      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
     };
     if (!r.few(l))
       count ? launch(k_fwd_level<true>) : launch(k_fwd_level<false>);
@@ -557,15 +563,15 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
       for (int l = depth; l >= 0; --l) {
-        const bool sweep = l == depth || (!r.few(l) && r.with_successors(l) < kFewLanes);
-        if (sweep) {
+        const bool adds = r.coef_from_forward(l, depth);
+        if (adds && l == 0) {  // no forward launch for level 0: every source is depth 0 (no links)
           ProfScope ps(t, PROF_BWD_INIT, st, l);
           k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
         }
         if (l == depth) continue;
-        ProfScope ps(t, sweep || r.few(l) ? PROF_BWD_FEW : PROF_BWD, st, l);
+        ProfScope ps(t, adds || r.few(l) ? PROF_BWD_FEW : PROF_BWD, st, l);
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
-        if (sweep)
+        if (adds)
           launch(k_bwd_few<true, true>);
         else if (!r.few(l))
           launch(k_bwd_level);
