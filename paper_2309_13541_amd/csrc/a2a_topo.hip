@@ -216,6 +216,9 @@ int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
 // k_bwd_few for those sources only.
 constexpr double kFewLanes = 8.0;
 constexpr double kSlotLanes = 2.0;
+// Largest topology: a batch's value array (N * 64 entries of 8 bytes) is addressed with 32-bit
+// byte offsets.
+constexpr int32_t kMaxNodes = 4 * 1024 * 1024;
 
 struct Run {
   const a2a_topo* t;
@@ -391,6 +394,7 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
   if (!out) return A2A_ERR_INVALID_ARG;
   *out = nullptr;
   if (N <= 0 || !row_ptr || row_ptr[0] != 0) return A2A_ERR_INVALID_ARG;
+  if (N > kMaxNodes) return A2A_ERR_NOT_IMPLEMENTED;
   int32_t dmax = 0;
   for (int32_t u = 0; u < N; ++u) {
     if (row_ptr[u + 1] < row_ptr[u]) return A2A_ERR_INVALID_ARG;

@@ -70,6 +70,8 @@ def test_create_validates_before_any_device_call(a2a):
     assert _create(a2a, 9, rp, bad) == a2a.ERR_SELF_LOOP
     lib = a2a.load_library()
     assert lib.a2a_topo_create(9, rp.ctypes.data, col.ctypes.data, None) == a2a.ERR_INVALID_ARG
+    # more hosts than the 32-bit offsets of a batch's arrays cover: refused before row_ptr is walked
+    assert _create(a2a, 4 * 1024 * 1024 + 1, rp, col) == a2a.ERR_NOT_IMPLEMENTED
     # well-formed input: ok on a GPU machine, a HIP error (never a crash) without a device
     assert _create(a2a, 9, rp, col) in (a2a.OK, a2a.ERR_HIP)
 
