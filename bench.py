@@ -35,6 +35,8 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
     proportion to their links) + 8 B read (ordered reduction).
     A launch at level l is charged the pairs of level l and the links into (forward) or out of
     (backward) that level; which kernel class ran the level comes from the per-level timings.
+    Where the forward launch also leaves coef = 1/sigma behind (deepest level; well-filled
+    level with sparse successors), the node's own 16 backward bytes are charged to it.
     """
     L = len(prof["pairs_level"])
     pairs = [p / steps for p in prof["pairs_level"]]       # per step
@@ -46,17 +48,22 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
     for l in range(L):
         if ran["bfs"][l]:
             out["bfs"] += 1 * pairs[l]
-        for k in ("fwd_rows", "fwd_few"):
-            if ran[k][l]:
-                out[k] += (1 + 8) * pairs[l] + 8 * dag_in[l]
-        part = 8.0 * nb * E * dag_out[l] / dag_total
+        fwd = next((k for k in ("fwd_rows", "fwd_few") if ran[k][l]), None)
+        if fwd:
+            out[fwd] += (1 + 8) * pairs[l] + 8 * dag_in[l]
+        own = (8 + 8) * pairs[l]                      # sigma read + coef written at the node itself
+        links = 8 * dag_out[l] + 8.0 * nb * E * dag_out[l] / dag_total
         if ran["bwd_rows"][l]:
-            out["bwd_rows"] += (8 + 8) * pairs[l] + 8 * dag_out[l] + part
+            out["bwd_rows"] += own + links
+            continue
+        if ran["bwd_few"][l]:
+            out["bwd_few"] += links
         if ran["bwd_init"][l]:
-            out["bwd_init"] += (8 + 8) * pairs[l]
-        if ran["bwd_few"][l]:  # after a sweep the level's own entries are charged to the sweep
-            own = 0 if ran["bwd_init"][l] else (8 + 8) * pairs[l]
-            out["bwd_few"] += own + 8 * dag_out[l] + part
+            out["bwd_init"] += own
+        elif ran["bwd_few"][l] and fwd != "fwd_rows":  # few sources per node: the kernel writes coef itself
+            out["bwd_few"] += own
+        elif fwd:                                      # the forward launch left 1/sigma in coef
+            out[fwd] += own
     out["reduce"] = 8.0 * nb * E
     return out
 
