@@ -44,7 +44,7 @@ typedef enum a2a_status {
   A2A_ERR_SELF_LOOP = -2,           /* a link u -> u (generators drop them before create) */
   A2A_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace cannot hold one batch of 64 sources */
   A2A_ERR_HIP = -4,                 /* a HIP runtime call failed (no device, out of memory ...) */
-  A2A_ERR_NOT_IMPLEMENTED = -5,     /* N above 4 194 048 nodes (32-bit offsets into the value arrays) */
+  A2A_ERR_NOT_IMPLEMENTED = -5,     /* N above 4 194 304 nodes (32-bit offsets into a batch's arrays) */
   A2A_ERR_DISCONNECTED = -6,        /* some ordered pair has no path: all-to-all infeasible */
   A2A_ERR_NO_MEMORY = -7,           /* host allocation failed */
   A2A_ERR_LEVEL_OVERFLOW = -8       /* BFS went deeper than the level bound of the handle */
@@ -63,7 +63,7 @@ typedef enum a2a_status {
 
 /*
  * Validates the CSR, builds the in-neighbour CSR (stable in link-id order) and uploads both.
- *   N        number of hosts, 0 < N <= 4 194 048 (more: A2A_ERR_NOT_IMPLEMENTED)
+ *   N        number of hosts, 0 < N <= 4 194 304 (more: A2A_ERR_NOT_IMPLEMENTED)
  *   row_ptr  host, int32[N+1], row_ptr[0] = 0, non-decreasing, row_ptr[N] = E (E may be 0)
  *   col_idx  host, int32[E], each in [0,N); parallel links allowed, self-loops rejected
  *   out      receives the handle; release with a2a_topo_destroy

@@ -12,11 +12,6 @@
 // where delta is the traffic forwarded through v under the equal split of Sec. 5.2.  A link (u,w) is used by the sources
 // in L_l[u] & L_{l+1}[w]; a gather of row (l,u) therefore reads popcount(L_l[u]) values instead
 // of a 64-wide row, and a node's row is written once per pass instead of once per level.
-//
-// Two consecutive batches ("halves", 128 sources) form a wide batch and share one value array:
-// the row of (l, v) is the entries of half 0 followed by those of half 1.  A wave works on a
-// node for both halves back to back, so that the memory lines a row spans are fetched once for
-// 128 sources, and one 32-byte index entry serves both.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -221,17 +216,16 @@ constexpr int kBfsWaves = kBfsBlock / kWave;
 struct GroupView {
   uint64_t* bm;       // [SB][Lcap][Npad][kSub] BFS level masks L_l[v]
   uint64_t* seen;     // [SB][Npad][kSub]
-  NodeIdx* idxw;      // [GW][Lcap][Npad][2]  mask + row offset of both halves (nullptr: distances only)
-  double* dat;        // [GW][cap]  level-compact sigma (nullptr: distances only)
-  double* coef;       // [GW][cap]  level-compact coef (link loads only)
-  int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level; after
-                      //                       k_scan_blocks, half 0: first entry of the block's rows
+  NodeIdx* idxb;      // [G][Lcap][Npad]  mask + row offset per batch (nullptr: distances only)
+  double* dat;        // [G][Npad*64]  level-compact sigma (nullptr: distances only)
+  double* coef;       // [G][Npad*64]  level-compact coef (link loads only)
+  int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level;
+                      //                       after k_scan_blocks: first entry of the block's rows
   long long* ltot;    // [SB*kSub][Lcap]   newly reached pairs per level
-  long long* dag;     // [GW][Lcap]     (source, link) pairs into each level (profiling mode 2)
-  double* part;       // [GW][Epad]     link loads per wide batch
+  long long* dag;     // [G][Lcap]      (source, link) pairs into each level (profiling mode 2)
+  double* part;       // [G][Epad]      per-batch link loads
   size_t Epad;
-  size_t cap;         // entries of a wide batch's value array = 2 * Npad * 64
-  int N, Npad, Lcap, G, GW, SB, bpb, nb64, inflight;  // G batches = GW wide batches (last may be half)
+  int N, Npad, Lcap, G, SB, bpb, nb64, inflight;
   int src_begin, src_count, batch0;
 };
 
@@ -244,7 +238,7 @@ __device__ __forceinline__ size_t bm_at(const GroupView& gv, int sb, int level, 
 // ---------------------------------------------------------------------------------------
 
 // Level 0: bit j of L_0[s_j] and seen[s_j] for the batch's sources s_j; sigma(s_j,s_j) = 1 is
-// entry j (half 0) or 64 + j (half 1) of the wide batch's value array.  One thread per (node, batch of the super-batch).
+// entry j of the value array.  One thread per (node, batch of the super-batch).
 __global__ void __launch_bounds__(kBfsBlock) k_init_group(GroupView gv) {
   int sb, nblk;
   if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
@@ -259,11 +253,11 @@ __global__ void __launch_bounds__(kBfsBlock) k_init_group(GroupView gv) {
   const uint64_t bit = is_src ? (1ull << j) : 0ull;
   gv.bm[bm_at(gv, sb, 0, v, k)] = bit;
   gv.seen[((size_t)sb * gv.Npad + v) * kSub + k] = bit;
-  if (gv.dat != nullptr && is_src) gv.dat[(size_t)(g >> 1) * gv.cap + (g & 1) * 64 + j] = 1.0;
+  if (gv.dat != nullptr && is_src) gv.dat[(size_t)g * gv.Npad * 64 + j] = 1.0;
   if (v == 0) {
     gv.ltot[(size_t)g * gv.Lcap] = cnt;
-    if (g < gv.G && (g & 1) == 0)
-      for (int l = 0; l < gv.Lcap; ++l) gv.dag[(size_t)(g >> 1) * gv.Lcap + l] = 0;
+    if (g < gv.G)
+      for (int l = 0; l < gv.Lcap; ++l) gv.dag[(size_t)g * gv.Lcap + l] = 0;
   }
 }
 
@@ -313,31 +307,28 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   }
 }
 
-// bsum[g][l][*] (pairs per 64-node block) of the two halves -> position of the block's first row
-// in the wide batch's value array (left in half 0's bsum): exclusive prefix over blocks, after
-// all rows of the levels above.  One wave per (wide batch, level), levels 1..depth.
+// bsum[g][l][*] (pairs per 64-node block) -> position of the block's first row in the batch's
+// value array: exclusive prefix over blocks, after all rows of the levels above.  One wave per
+// (batch, level), levels 1..depth.
 __global__ void __launch_bounds__(kWave) k_scan_blocks(GroupView gv, int depth) {
-  const int w = (int)blockIdx.x / depth, level = 1 + (int)blockIdx.x % depth;
+  const int g = (int)blockIdx.x / depth, level = 1 + (int)blockIdx.x % depth;
   const int lane = lane_id();
-  const long long* __restrict__ lt0 = gv.ltot + (size_t)(2 * w) * gv.Lcap;
-  const long long* __restrict__ lt1 = lt0 + gv.Lcap;
+  const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
   long long carry = 0;
-  for (int l = 0; l < level; ++l) carry += lt0[l] + lt1[l];
-  int* __restrict__ bs0 = gv.bsum + ((size_t)(2 * w) * gv.Lcap + level) * gv.nb64;
-  const int* __restrict__ bs1 = bs0 + (size_t)gv.Lcap * gv.nb64;
+  for (int l = 0; l < level; ++l) carry += lt[l];
+  int* __restrict__ bs = gv.bsum + ((size_t)g * gv.Lcap + level) * gv.nb64;
   for (int b0 = 0; b0 < gv.nb64; b0 += kWave) {
     const int b = b0 + lane;
-    const int c = b < gv.nb64 ? bs0[b] + bs1[b] : 0;
+    const int c = b < gv.nb64 ? bs[b] : 0;
     const int incl = wave_scan_incl(c, lane);
-    if (b < gv.nb64) bs0[b] = (int)(carry + incl - c);
+    if (b < gv.nb64) bs[b] = (int)(carry + incl - c);
     carry += __shfl(incl, kWave - 1, kWave);
   }
 }
 
-// Index array from the BFS masks: idxw[w][l][v][h] = { L_l[v] of half h, first entry of its row }.
-// Thread (node, k) as in the BFS; lanes k and k ^ 1 are the halves of a wide batch.  The row
-// offsets are an exclusive prefix over nodes of the two halves' counts (three shuffle steps
-// across the 8 nodes of a wave, then across the 8 waves via LDS); half 1 follows half 0.
+// Index array from the BFS masks: idxb[g][l][v] = { L_l[v], first entry of the row }.
+// Thread (node, k) as in the BFS; the row offsets are an exclusive prefix over nodes for each
+// batch k (three shuffle steps across the 8 nodes of a wave, then across the 8 waves via LDS).
 __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int depth) {
   int sb, nblk;
   if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
@@ -352,12 +343,10 @@ __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int d
     n.mask = m;
     n.pad = 0;
     if (l == 0) {
-      n.off = (uint32_t)((k & 1) * 64) + (m ? (uint32_t)__builtin_ctzll(m) : 0u);  // source j owns entry j
+      n.off = m ? (uint32_t)__builtin_ctzll(m) : 0u;  // source j owns entry j
     } else {
       const int c = __popcll(m);
-      const int c_other = __shfl_xor(c, 1, kWave);
-      const int cw = c + c_other;
-      int x = cw;  // inclusive prefix over the wave's nodes, per wide batch
+      int x = c;  // inclusive prefix over the wave's nodes, per batch
       int y = __shfl_up(x, 8, kWave);
       if (lane >= 8) x += y;
       y = __shfl_up(x, 16, kWave);
@@ -366,17 +355,16 @@ __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int d
       if (lane >= 32) x += y;
       if (lane >= kWave - kSub) s_w[wid][k] = x;
       __syncthreads();
-      int base = (g & ~1) < gv.G ? gv.bsum[((size_t)(g & ~1) * gv.Lcap + l) * gv.nb64 + nblk] : 0;
+      int base = g < gv.G ? gv.bsum[((size_t)g * gv.Lcap + l) * gv.nb64 + nblk] : 0;
       for (int w = 0; w < wid; ++w) base += s_w[w][k];
-      n.off = (uint32_t)(base + x - cw + ((k & 1) ? c_other : 0));
+      n.off = (uint32_t)(base + x - c);
       __syncthreads();
     }
-    // transpose through LDS: wave w writes the 64 entries of batch sb*kSub+w (stride: two halves)
+    // transpose through LDS: wave w writes the 64 consecutive entries of batch sb*kSub+w
     s_n[k][t / kSub] = n;
     __syncthreads();
     const int gw = sb * kSub + wid;
-    if ((gw >> 1) < gv.GW)
-      gv.idxw[((((size_t)(gw >> 1) * gv.Lcap + l) * gv.Npad) + nblk * kBfsNodes + lane) * 2 + (gw & 1)] = s_n[wid][lane];
+    if (gw < gv.G) gv.idxb[((size_t)gw * gv.Lcap + l) * gv.Npad + nblk * kBfsNodes + lane] = s_n[wid][lane];
     __syncthreads();
   }
 }
@@ -385,24 +373,20 @@ __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int d
 // forward: path counts
 // ---------------------------------------------------------------------------------------
 
-// --- well-filled levels: one wave per (wide batch, node) ---------------------------------
+// --- well-filled levels: one wave per (batch, node) -------------------------------------
 //
-// A wave owns 64 consecutive nodes of one wide batch; lane j = source j of the half being worked
-// on.  It works through the nodes eight at a time ("group"): the 64 lanes first fetch
-// (neighbour, masks, offsets) for 8 nodes x 8 links at once (an "index tile": lane 8i+j looks
-// at link j of node i), then each node's sources gather from the compact rows of its links,
-// half 0 and then half 1.  Three things keep enough memory requests in flight: the neighbour ids
-// of the group after next and the index tile of the next group are requested while the current
-// group is worked on, and the eight row gathers of the next (node, half) are issued before the
-// values of the current one are used.  Nodes with more than 8 links take further, unpipelined,
-// rounds.
+// A wave owns 64 consecutive nodes of one batch; lane j = source j.  It works through the nodes
+// eight at a time ("group"): the 64 lanes first fetch (neighbour, mask, offset) for 8 nodes x 8
+// links at once (an "index tile": lane 8i+j looks at link j of node i), then each node's
+// sources gather from the compact rows of its links.  Three things keep enough memory requests
+// in flight: the neighbour ids of the group after next and the index tile of the next group are
+// requested while the current group is worked on, and the eight row gathers of node i+1 are
+// issued before the values of node i are used.  Nodes with more than 8 links take further,
+// unpipelined, rounds.
 
 struct Tile {
-  uint64_t mask;  // L[neighbour] of this lane's link, one half (0: no link)
+  uint64_t mask;  // L[neighbour] of this lane's link (0: no link)
   uint32_t off;   // its row offset
-};
-struct Tile2 {
-  Tile h0, h1;  // the two halves
 };
 
 // In- or out-link range of the 64 nodes, one node per lane; nothing for nodes not on this level.
@@ -419,23 +403,16 @@ __device__ __forceinline__ int tile_request_col(const int32_t* __restrict__ col,
   return q >= 0 ? col[q] : -1;
 }
 
-__device__ __forceinline__ Tile2 tile_request_idx(const NodeIdx* __restrict__ level, int nb) {
-  Tile2 t;
-  t.h0.mask = t.h1.mask = 0;
-  t.h0.off = t.h1.off = 0;
+__device__ __forceinline__ Tile tile_request_idx(const NodeIdx* __restrict__ level, int nb) {
+  Tile t;
+  t.mask = 0;
+  t.off = 0;
   if (nb >= 0) {
-    const NodeIdx n0 = load_idx(level + 2 * (size_t)nb), n1 = load_idx(level + 2 * (size_t)nb + 1);
-    t.h0.mask = n0.mask;
-    t.h0.off = n0.off;
-    t.h1.mask = n1.mask;
-    t.h1.off = n1.off;
+    const NodeIdx n = load_idx(level + nb);
+    t.mask = n.mask;
+    t.off = n.off;
   }
   return t;
-}
-
-// The arrays of wide batch w at a level: index entries of node v at [2 v], [2 v + 1].
-__device__ __forceinline__ const NodeIdx* idx_level(const GroupView& gv, int w, int level) {
-  return gv.idxw + (((size_t)w * gv.Lcap + level) * gv.Npad) * 2;
 }
 
 // Issues the (up to) eight row gathers of node i of the current tile: lanes in mk & want read
@@ -480,56 +457,53 @@ template <bool kCountDag>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
             int level, bool init_coef, long long* __restrict__ misc) {
-  int w, nblk;
-  if (!map_block(gv.GW, gv.bpb, gv.inflight, w, nblk)) return;
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
   const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (v0 >= gv.N) return;
-  const NodeIdx* __restrict__ cur = idx_level(gv, w, level);
-  const NodeIdx* __restrict__ prev = idx_level(gv, w, level - 1);
-  double* __restrict__ dat = gv.dat + (size_t)w * gv.cap;
-  double* __restrict__ cf = init_coef ? gv.coef + (size_t)w * gv.cap : nullptr;
-  const NodeIdx me0 = load_idx(cur + 2 * (size_t)(v0 + lane)), me1 = load_idx(cur + 2 * (size_t)(v0 + lane) + 1);
-  const uint64_t nodes_active = __ballot((me0.mask | me1.mask) != 0);
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
+  const NodeIdx me = load_idx(cur + v0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
   LinkRange lr;
   lr.p0 = lr.p1 = 0;
-  if ((me0.mask | me1.mask) != 0) {
+  if (me.mask != 0) {
     lr.p0 = in_ptr[v0 + lane];
     lr.p1 = in_ptr[v0 + lane + 1];
   }
   bool inexact = false;
   long long dag = 0;
   int q;
-  Tile2 tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
   int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
 #pragma unroll 1
   for (int c = 0; c < 8; ++c) {
-    const Tile2 tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
+    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
     nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       double xa[8], xb[8];
       uint64_t m[8];
-      int pairs = gather8(dat, tile.h0, 0, readlane64(me0.mask, 8 * c), xa, m);
+      int pairs = gather8(dat, tile, 0, readlane64(me.mask, 8 * c), xa, m);
 #pragma unroll 1
-      for (int i = 0; i < 8; ++i) {  // a node per round, half 0 then half 1; the next rows always in flight
-        pairs += gather8(dat, tile.h1, i, readlane64(me1.mask, 8 * c + i), xb, m);
-        inexact |= fwd_finish(dat, cf, me0, 8 * c + i, xa);
-        if (i + 1 < 8) pairs += gather8(dat, tile.h0, i + 1, readlane64(me0.mask, 8 * c + i + 1), xa, m);
-        inexact |= fwd_finish(dat, cf, me1, 8 * c + i, xb);
+      for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
+        pairs += gather8(dat, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
+        inexact |= fwd_finish(dat, cf, me, 8 * c + i, xa);
+        if (i + 2 < 8) pairs += gather8(dat, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
+        inexact |= fwd_finish(dat, cf, me, 8 * c + i + 1, xb);
       }
       if (kCountDag) dag += pairs;
       // nodes with more than eight in-links: add the rest to the stored entries
       const int p0 = __shfl(lr.p0, 8 * c + (lane >> 3), kWave), p1 = __shfl(lr.p1, 8 * c + (lane >> 3), kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
-        const Tile2 extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
+        const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
 #pragma unroll 1
-        for (int ih = 0; ih < 16; ++ih) {
-          const int i = ih >> 1;
-          const bool h1 = ih & 1;
-          const NodeIdx& me = h1 ? me1 : me0;
+        for (int i = 0; i < 8; ++i) {
           const uint64_t newv = readlane64(me.mask, 8 * c + i);
-          const int np = gather8(dat, h1 ? extra.h1 : extra.h0, i, newv, xa, m);
+          const int np = gather8(dat, extra, i, newv, xa, m);
           if (np == 0) continue;
           if (kCountDag) dag += np;
           double a = 0.0;
@@ -550,7 +524,7 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   }
   if (inexact) misc[0] = 1;
   if (kCountDag && dag != 0 && lane == 0)
-    atomicAdd((unsigned long long*)&gv.dag[(size_t)w * gv.Lcap + level], (unsigned long long)dag);
+    atomicAdd((unsigned long long*)&gv.dag[(size_t)g * gv.Lcap + level], (unsigned long long)dag);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -560,14 +534,14 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
 // One level of coef(s,u) = 1/sigma(s,u) + sum over out-links (u,w) with D(s,w) = D(s,u) + 1 of
 // coef(s,w), and load(u,w) += sum over sources of sigma(s,u) * coef(s,w): the share of the unit
 // demands that the equal split over shortest paths (Sec. 5.2) routes over the link.  After the
-// eight-way wave reduction lane 8i+j holds the load of out-link j of node i (tot_l, summed over
-// the two halves), which is the lane that fetched that link's id: one coalesced
-// read-modify-write of the wide batch's link loads per group.
+// eight-way wave reduction lane 8i+j holds the load of out-link j of node i, which is the lane
+// that fetched that link's id: one coalesced read-modify-write of the batch's link loads per
+// group.
 __device__ __forceinline__ double link_sums(double (&x)[8], const uint64_t (&m)[8], int pairs, int i, int lane,
                                             double tot_l, double* sum8_buf) {
   if (pairs > kSerialPairs) {
     const double tot = wave_sum8_lds(x, lane, sum8_buf);  // lane l: load of link (l & 7) of node i
-    if ((lane >> 3) == i) tot_l += tot;
+    if ((lane >> 3) == i) tot_l = tot;
   } else {
     // few (source, link) pairs: pick the products out lane by lane instead of reducing
 #pragma unroll
@@ -580,7 +554,7 @@ __device__ __forceinline__ double link_sums(double (&x)[8], const uint64_t (&m)[
         mm &= mm - 1;
         sum += __longlong_as_double((long long)readlane64((uint64_t)__double_as_longlong(x[j]), l));
       }
-      if (lane == 8 * i + j) tot_l += sum;
+      if (lane == 8 * i + j) tot_l = sum;
     }
   }
   return tot_l;
@@ -619,33 +593,33 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
 __global__ void __launch_bounds__(kBlock)
 k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
             int level) {
-  int w, nblk;
-  if (!map_block(gv.GW, gv.bpb, gv.inflight, w, nblk)) return;
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
   const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (u0 >= gv.N) return;
-  const NodeIdx* __restrict__ cur = idx_level(gv, w, level);
-  const NodeIdx* __restrict__ next = idx_level(gv, w, level + 1);
-  const double* __restrict__ dat = gv.dat + (size_t)w * gv.cap;
-  double* __restrict__ cf = gv.coef + (size_t)w * gv.cap;
-  double* __restrict__ pt = gv.part + (size_t)w * gv.Epad;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
+  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   __shared__ double s_sum8[kWavesPerBlock][kSum8Doubles];
   double* sum8_buf = s_sum8[threadIdx.x / kWave];
-  const NodeIdx me0 = load_idx(cur + 2 * (size_t)(u0 + lane)), me1 = load_idx(cur + 2 * (size_t)(u0 + lane) + 1);
-  const uint64_t nodes_active = __ballot((me0.mask | me1.mask) != 0);
+  const NodeIdx me = load_idx(cur + u0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
   LinkRange lr;
   lr.p0 = lr.p1 = 0;
-  if ((me0.mask | me1.mask) != 0) {
+  if (me.mask != 0) {
     lr.p0 = out_ptr[u0 + lane];
     lr.p1 = out_ptr[u0 + lane + 1];
   }
   int q, q_next, q_nn;
-  Tile2 tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
   int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
 #pragma unroll 1
   for (int c = 0; c < 8; ++c) {
-    const Tile2 tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
     nb_next = -1;
     q_nn = -1;
     if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
@@ -653,39 +627,35 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
       double xa[8], xb[8];
       uint64_t ma[8], mb[8];
       double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i
-      double sa = own_sigma(dat, me0, 8 * c), sb;
-      int pa = gather8(cf, tile.h0, 0, readlane64(me0.mask, 8 * c), xa, ma), pb;
+      double sa = own_sigma(dat, me, 8 * c), sb;
+      int pa = gather8(cf, tile, 0, readlane64(me.mask, 8 * c), xa, ma), pb;
 #pragma unroll 1
-      for (int i = 0; i < 8; ++i) {  // a node per round, half 0 then half 1; the next rows always in flight
-        sb = own_sigma(dat, me1, 8 * c + i);
-        pb = gather8(cf, tile.h1, i, readlane64(me1.mask, 8 * c + i), xb, mb);
-        tot_l = bwd_finish(cf, me0, 8 * c + i, i, sa, xa, ma, pa, false, lane, tot_l, sum8_buf);
-        if (i + 1 < 8) {
-          sa = own_sigma(dat, me0, 8 * c + i + 1);
-          pa = gather8(cf, tile.h0, i + 1, readlane64(me0.mask, 8 * c + i + 1), xa, ma);
+      for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
+        sb = own_sigma(dat, me, 8 * c + i + 1);
+        pb = gather8(cf, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, mb);
+        tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, false, lane, tot_l, sum8_buf);
+        if (i + 2 < 8) {
+          sa = own_sigma(dat, me, 8 * c + i + 2);
+          pa = gather8(cf, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, ma);
         }
-        tot_l = bwd_finish(cf, me1, 8 * c + i, i, sb, xb, mb, pb, false, lane, tot_l, sum8_buf);
+        tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, xb, mb, pb, false, lane, tot_l, sum8_buf);
       }
-      const int node = 8 * c + (lane >> 3);
-      const uint64_t mu0 = shfl64(me0.mask, node), mu1 = shfl64(me1.mask, node);
-      if (q >= 0 && ((tile.h0.mask & mu0) | (tile.h1.mask & mu1)) != 0) pt[q] += tot_l;
+      const uint64_t mu_lane = shfl64(me.mask, 8 * c + (lane >> 3));
+      if (q >= 0 && (tile.mask & mu_lane) != 0) pt[q] += tot_l;
       // nodes with more than eight out-links: add the rest to the stored coef
-      const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
+      const int p0 = __shfl(lr.p0, 8 * c + (lane >> 3), kWave), p1 = __shfl(lr.p1, 8 * c + (lane >> 3), kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         int qe;
-        const Tile2 extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
+        const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
         tot_l = 0.0;
 #pragma unroll 1
-        for (int ih = 0; ih < 16; ++ih) {
-          const int i = ih >> 1;
-          const bool h1 = ih & 1;
-          const NodeIdx& me = h1 ? me1 : me0;
-          pa = gather8(cf, h1 ? extra.h1 : extra.h0, i, readlane64(me.mask, 8 * c + i), xa, ma);
+        for (int i = 0; i < 8; ++i) {
+          pa = gather8(cf, extra, i, readlane64(me.mask, 8 * c + i), xa, ma);
           if (pa == 0) continue;
           sa = own_sigma(dat, me, 8 * c + i);
           tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, true, lane, tot_l, sum8_buf);
         }
-        if (qe >= 0 && ((extra.h0.mask & mu0) | (extra.h1.mask & mu1)) != 0) pt[qe] += tot_l;
+        if (qe >= 0 && (extra.mask & mu_lane) != 0) pt[qe] += tot_l;
       }
     }
     tile = tile_next;
@@ -919,50 +889,45 @@ template <bool kCountDag, bool kSlots>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
           bool init_coef, long long* __restrict__ misc) {
-  int w, nblk;
-  if (!map_block(gv.GW, gv.bpb, gv.inflight, w, nblk)) return;
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
   const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (v0 >= gv.N) return;
-  const NodeIdx* __restrict__ cur = idx_level(gv, w, level);
-  const NodeIdx* __restrict__ prev = idx_level(gv, w, level - 1);
-  double* __restrict__ dat = gv.dat + (size_t)w * gv.cap;
-  double* __restrict__ cf = init_coef ? gv.coef + (size_t)w * gv.cap : nullptr;
-  const NodeIdx me0 = load_idx(cur + 2 * (size_t)(v0 + lane)), me1 = load_idx(cur + 2 * (size_t)(v0 + lane) + 1);
-  const uint64_t nodes_active = __ballot((me0.mask | me1.mask) != 0);
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
+  const NodeIdx me = load_idx(cur + v0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
   LinkRange lr;
   lr.p0 = lr.p1 = 0;
-  if ((me0.mask | me1.mask) != 0) {
+  if (me.mask != 0) {
     lr.p0 = in_ptr[v0 + lane];
     lr.p1 = in_ptr[v0 + lane + 1];
   }
   bool inexact = false;
   int dag = 0;
   int q;
-  Tile2 tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
   int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
-  auto one = [&](const Tile& tl, uint64_t mu, uint32_t ofu, bool add) {
-    inexact |= kSlots ? slot_fwd(dat, cf, tl, mu, ofu, add, lane) : few_fwd(dat, cf, tl, mu, ofu, add, lane);
-    if (kCountDag) dag += __popcll(tl.mask & mu);
-  };
 #pragma unroll 1
   for (int c = 0; c < 8; ++c) {
-    const Tile2 tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
+    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
     nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       const int node = 8 * c + (lane >> 3);
-      const uint64_t mu0 = shfl64(me0.mask, node), mu1 = shfl64(me1.mask, node);
-      const uint32_t ofu0 = (uint32_t)__shfl((int)me0.off, node, kWave);
-      const uint32_t ofu1 = (uint32_t)__shfl((int)me1.off, node, kWave);
-      one(tile.h0, mu0, ofu0, false);
-      one(tile.h1, mu1, ofu1, false);
+      const uint64_t mu = shfl64(me.mask, node);
+      const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
+      inexact |= kSlots ? slot_fwd(dat, cf, tile, mu, ofu, false, lane) : few_fwd(dat, cf, tile, mu, ofu, false, lane);
+      if (kCountDag) dag += __popcll(tile.mask & mu);
       // nodes with more than eight in-links: add the rest to the stored entries
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
-        const Tile2 extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
-        one(extra.h0, mu0, ofu0, true);
-        one(extra.h1, mu1, ofu1, true);
+        const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
+        inexact |= kSlots ? slot_fwd(dat, cf, extra, mu, ofu, true, lane) : few_fwd(dat, cf, extra, mu, ofu, true, lane);
+        if (kCountDag) dag += __popcll(extra.mask & mu);
       }
     }
     tile = tile_next;
@@ -971,60 +936,56 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
   if (kCountDag) {
     dag = wave_sum_int(dag);
     if (dag != 0 && lane == 0)
-      atomicAdd((unsigned long long*)&gv.dag[(size_t)w * gv.Lcap + level], (unsigned long long)dag);
+      atomicAdd((unsigned long long*)&gv.dag[(size_t)g * gv.Lcap + level], (unsigned long long)dag);
   }
 }
 
 template <bool kSlots, bool kUnion>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
-  int w, nblk;
-  if (!map_block(gv.GW, gv.bpb, gv.inflight, w, nblk)) return;
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
   const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (u0 >= gv.N) return;
-  const NodeIdx* __restrict__ cur = idx_level(gv, w, level);
-  const NodeIdx* __restrict__ next = idx_level(gv, w, level + 1);
-  const double* __restrict__ dat = gv.dat + (size_t)w * gv.cap;
-  double* __restrict__ cf = gv.coef + (size_t)w * gv.cap;
-  double* __restrict__ pt = gv.part + (size_t)w * gv.Epad;
-  const NodeIdx me0 = load_idx(cur + 2 * (size_t)(u0 + lane)), me1 = load_idx(cur + 2 * (size_t)(u0 + lane) + 1);
-  const uint64_t nodes_active = __ballot((me0.mask | me1.mask) != 0);
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
+  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const NodeIdx me = load_idx(cur + u0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
   LinkRange lr;
   lr.p0 = lr.p1 = 0;
-  if ((me0.mask | me1.mask) != 0) {
+  if (me.mask != 0) {
     lr.p0 = out_ptr[u0 + lane];
     lr.p1 = out_ptr[u0 + lane + 1];
   }
   int q, q_next, q_nn;
-  Tile2 tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
   int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
-  auto one = [&](const Tile& tl, uint64_t mu, uint32_t ofu, bool add) {
-    return kSlots ? slot_bwd<kUnion>(dat, cf, tl, mu, ofu, add, lane) : few_bwd(dat, cf, tl, mu, ofu, add, lane);
-  };
 #pragma unroll 1
   for (int c = 0; c < 8; ++c) {
-    const Tile2 tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
     nb_next = -1;
     q_nn = -1;
     if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       const int node = 8 * c + (lane >> 3);
-      const uint64_t mu0 = shfl64(me0.mask, node), mu1 = shfl64(me1.mask, node);
-      const uint32_t ofu0 = (uint32_t)__shfl((int)me0.off, node, kWave);
-      const uint32_t ofu1 = (uint32_t)__shfl((int)me1.off, node, kWave);
-      double tot = one(tile.h0, mu0, ofu0, false);
-      tot += one(tile.h1, mu1, ofu1, false);
-      if (q >= 0 && ((tile.h0.mask & mu0) | (tile.h1.mask & mu1)) != 0) pt[q] += tot;
+      const uint64_t mu = shfl64(me.mask, node);
+      const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
+      const double tot =
+          kSlots ? slot_bwd<kUnion>(dat, cf, tile, mu, ofu, false, lane) : few_bwd(dat, cf, tile, mu, ofu, false, lane);
+      if (q >= 0 && (tile.mask & mu) != 0) pt[q] += tot;
       // nodes with more than eight out-links: add the rest to the stored coef
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         int qe;
-        const Tile2 extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
-        double te = one(extra.h0, mu0, ofu0, true);
-        te += one(extra.h1, mu1, ofu1, true);
-        if (qe >= 0 && ((extra.h0.mask & mu0) | (extra.h1.mask & mu1)) != 0) pt[qe] += te;
+        const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
+        const double te =
+            kSlots ? slot_bwd<kUnion>(dat, cf, extra, mu, ofu, true, lane) : few_bwd(dat, cf, extra, mu, ofu, true, lane);
+        if (qe >= 0 && (extra.mask & mu) != 0) pt[qe] += te;
       }
     }
     tile = tile_next;
@@ -1038,15 +999,14 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
 __global__ void __launch_bounds__(kBfsBlock) k_bwd_init_level(GroupView gv, int level) {
   int sb, nblk;
   if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
-  const int g = sb * kSub + (int)threadIdx.x / kWave;  // the wave of half 0 sweeps the wide batch's slice
-  if (g >= gv.G || (g & 1) != 0) return;
-  const long long* __restrict__ lt0 = gv.ltot + (size_t)g * gv.Lcap;
-  const long long* __restrict__ lt1 = lt0 + gv.Lcap;
+  const int g = sb * kSub + (int)threadIdx.x / kWave;  // wave k sweeps batch k's slice
+  if (g >= gv.G) return;
+  const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
   long long base = 0;
-  for (int l = 0; l < level; ++l) base += lt0[l] + lt1[l];
-  const long long cnt = lt0[level] + lt1[level];
-  const double* __restrict__ dat = gv.dat + (size_t)(g >> 1) * gv.cap + base;
-  double* __restrict__ cf = gv.coef + (size_t)(g >> 1) * gv.cap + base;
+  for (int l = 0; l < level; ++l) base += lt[l];
+  const long long cnt = lt[level];
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64 + base;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64 + base;
   for (long long e = (long long)nblk * kWave + lane_id(); e < cnt; e += (long long)gv.nb64 * kWave)
     cf[e] = recip(dat[e]);
 }
@@ -1110,10 +1070,10 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
   __shared__ double t_s[kWave][kWave + 1];
   const int t = (int)threadIdx.x;
   const int v0 = tile * kWave;
-  const double* __restrict__ dat = gv.dat + (size_t)(g >> 1) * gv.cap;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   for (int i = 0; i < kWave; ++i) t_s[t][i] = 0.0;
   for (int l = 0; l <= depth; ++l) {
-    const NodeIdx me = load_idx(idx_level(gv, g >> 1, l) + 2 * (size_t)(v0 + t) + (g & 1));
+    const NodeIdx me = load_idx(gv.idxb + ((size_t)g * gv.Lcap + l) * gv.Npad + v0 + t);
     uint64_t todo = __ballot(me.mask != 0);
     while (todo) {
       const int i = __builtin_ctzll(todo);

@@ -72,14 +72,14 @@ struct Layout {
   size_t off_level_new = 0;  // int32 [Lcap]
   size_t off_misc = 0;       // int64 [8]: 0 sigma-inexact flag, 1 dist_sum, 2 reached pairs, 3 DAG links
   size_t off_ltot = 0;       // int64 [G][Lcap]
-  size_t off_dag = 0;        // int64 [GW][Lcap]        (GW = wide batches = pairs of batches)
+  size_t off_dag = 0;        // int64 [G][Lcap]
   size_t off_bsum = 0;       // int32 [SB*kSub][Lcap][nb64]
   size_t off_seen = 0;       // uint64 [SB][Npad][kSub]
   size_t off_bm = 0;         // uint64 [SB][Lcap][Npad][kSub]
-  size_t off_idxw = 0;       // NodeIdx [GW][Lcap][Npad][2]    (with sigma / loads)
-  size_t off_dat = 0;        // double [GW][2*Npad*64]  sigma
-  size_t off_coef = 0;       // double [GW][2*Npad*64]  coef (link loads only)
-  size_t off_part = 0;       // double [GW][Epad]
+  size_t off_idxb = 0;       // NodeIdx [G][Lcap][Npad]        (with sigma / loads)
+  size_t off_dat = 0;        // double [G][Npad*64]  sigma
+  size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
+  size_t off_part = 0;       // double [G][Epad]
   size_t total = 0;
 };
 
@@ -107,15 +107,14 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_misc = take(64);
     const size_t SB = (size_t)(G + kSub - 1) / kSub;
     const size_t o_ltot = take(SB * kSub * L.Lcap * 8);
-    const size_t GW = (size_t)(G + 1) / 2;
-    const size_t o_dag = take(GW * L.Lcap * 8);
+    const size_t o_dag = take((size_t)G * L.Lcap * 8);
     const size_t o_bsum = take(SB * kSub * L.Lcap * L.nb64 * 4);
     const size_t o_seen = take(SB * L.Npad * kSub * 8);
     const size_t o_bm = take(SB * L.Lcap * L.Npad * kSub * 8);
-    const size_t o_idxw = L.values ? take(GW * L.Lcap * L.Npad * 2 * sizeof(NodeIdx)) : 0;
-    const size_t o_dat = L.values ? take(GW * L.Npad * 128 * 8) : 0;
-    const size_t o_coef = L.loads ? take(GW * L.Npad * 128 * 8) : 0;
-    const size_t o_part = L.loads ? take(GW * L.Epad * 8) : 0;
+    const size_t o_idxb = L.values ? take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx)) : 0;
+    const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8) : 0;
+    const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8) : 0;
+    const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     if (out) {
       out->off_level_new = o_level_new;
       out->off_misc = o_misc;
@@ -125,7 +124,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->off_seen = o_seen;
       out->off_bm = o_bm;
       out->SB = (int)SB;
-      out->off_idxw = o_idxw;
+      out->off_idxb = o_idxb;
       out->off_dat = o_dat;
       out->off_coef = o_coef;
       out->off_part = o_part;
@@ -217,9 +216,9 @@ int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
 // k_bwd_few for those sources only.
 constexpr double kFewLanes = 8.0;
 constexpr double kSlotLanes = 2.0;
-// Largest topology: a wide batch's value array (N * 128 entries of 8 bytes) is addressed with
-// 32-bit byte offsets.
-constexpr int32_t kMaxNodes = 4 * 1024 * 1024 - 256;
+// Largest topology: a batch's value array (N * 64 entries of 8 bytes) is addressed with 32-bit
+// byte offsets.
+constexpr int32_t kMaxNodes = 4 * 1024 * 1024;
 
 struct Run {
   const a2a_topo* t;
@@ -248,7 +247,7 @@ struct Run {
   GroupView view(int batch0, int G) const {
     GroupView gv;
     gv.bm = (uint64_t*)(ws + L.off_bm);
-    gv.idxw = L.values ? (NodeIdx*)(ws + L.off_idxw) : nullptr;
+    gv.idxb = L.values ? (NodeIdx*)(ws + L.off_idxb) : nullptr;
     gv.seen = (uint64_t*)(ws + L.off_seen);
     gv.dat = L.values ? (double*)(ws + L.off_dat) : nullptr;
     gv.coef = L.loads ? (double*)(ws + L.off_coef) : nullptr;
@@ -261,8 +260,6 @@ struct Run {
     gv.Npad = L.Npad;
     gv.Lcap = L.Lcap;
     gv.G = G;
-    gv.GW = (G + 1) / 2;
-    gv.cap = (size_t)L.Npad * 128;
     gv.SB = (G + kSub - 1) / kSub;
     gv.bpb = L.bpb;
     gv.nb64 = L.nb64;
@@ -326,10 +323,10 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   const Layout& L = r.L;
   {
     ProfScope ps(t, PROF_OFFSETS, r.st);
-    if (depth >= 1) k_scan_blocks<<<(unsigned)(gv.GW * depth), kWave, 0, r.st>>>(gv, depth);
+    if (depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * depth), kWave, 0, r.st>>>(gv, depth);
     k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, depth);
   }
-  const unsigned grid = grid_for(gv.GW, L.bpb, r.inflight);
+  const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
     ProfScope ps(t, r.few(l) ? PROF_FWD_FEW : PROF_FWD, r.st, l);
     const bool count = t->prof_mode == 2;
@@ -348,10 +345,10 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   HIP_TRY(hipGetLastError());
   if (t->prof_mode == 2) {  // shortest-path links into each level, for the roofline accounting
     try {
-      std::vector<long long> dg((size_t)gv.GW * L.Lcap);
+      std::vector<long long> dg((size_t)gv.G * L.Lcap);
       HIP_TRY(hipMemcpyAsync(dg.data(), gv.dag, dg.size() * 8, hipMemcpyDeviceToHost, r.st));
       HIP_TRY(hipStreamSynchronize(r.st));
-      for (int g = 0; g < gv.GW; ++g)
+      for (int g = 0; g < gv.G; ++g)
         for (int l = 0; l <= depth; ++l)
           t->prof_dag_level[l < A2A_PROF_MAX_LEVELS ? l : A2A_PROF_MAX_LEVELS - 1] += dg[(size_t)g * L.Lcap + l];
     } catch (const std::bad_alloc&) {
@@ -567,8 +564,8 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     rc = run_fwd(r, gv, depth);
     if (rc != A2A_OK) return rc;
     if (t->E > 0) {
-      HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.GW * L.Epad * 8, st));
-      const unsigned grid = grid_for(gv.GW, L.bpb, r.inflight);
+      HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
+      const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
       for (int l = depth; l >= 0; --l) {
         const bool adds = r.coef_from_forward(l, depth);
         if (adds && l == 0) {  // no forward launch for level 0: every source is depth 0 (no links)
@@ -589,7 +586,7 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
       }
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(
-          gv.part, L.Epad, gv.GW, (long long)t->E, b0 == 0 ? 1 : 0, load);
+          gv.part, L.Epad, gv.G, (long long)t->E, b0 == 0 ? 1 : 0, load);
     }
     rc = run_fold(r, gv, depth);
     if (rc != A2A_OK) return rc;
