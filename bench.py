@@ -184,10 +184,11 @@ def main():
         cores = min(os.cpu_count() or 1, 16)
         sample = args.cpu_sources
         if sample is None:
-            # probe 32 sources per thread, then size the sample for about 15 s
+            # probe 32 sources per thread (start-up included, so it runs slow), then size the
+            # sample so that the timed run takes 10-20 s
             p = min(N, 32 * cores)
             tp = time.perf_counter(); oracle.run(rp, col, 0, p, threads=cores); tp = time.perf_counter() - tp
-            sample = int(max(p, min(N, p * 15.0 / max(tp, 1e-4))))
+            sample = int(max(p, min(N, p * 25.0 / max(tp, 1e-4))))
         tc = time.perf_counter()
         res = oracle.run(rp, col, 0, sample, threads=cores)
         tc = time.perf_counter() - tc
