@@ -153,6 +153,41 @@ int a2a_schedule_bound(const a2a_topo* topo, const double* load, int64_t sum_dis
                        double m_bytes, double b_bytes_per_s, a2a_bound* out, void* hip_stream);
 
 /*
+ * The same for a network G = (V, E, cap) with link capacities, the general form of the problem
+ * (Sec. 3.1.1; "a multiplier ... if link bandwidth is not uniform", Sec. 3.1.1 time-stepped LP):
+ * the flows of a routing fit when every link's load times the common rate stays within its
+ * capacity, so the all-to-all time of the EwSP routing is the largest utilisation load[a] / cap[a].
+ * cap[a] is the bandwidth of link a in units of b (cap = 1 everywhere gives a2a_schedule_bound).
+ *   cap        device, double[E], every entry positive and finite (else A2A_ERR_INVALID_ARG,
+ *              found on the device, `out` untouched)
+ *   other arguments as a2a_schedule_bound
+ * The capacity bound of Eq. (lb) is reported against the true total capacity (t_lb_links) and, as
+ * "d x N", against N nodes of the largest total out-capacity (t_lb_nd).  The total capacity is
+ * summed in a fixed order (reproducible from run to run).
+ */
+typedef struct a2a_bound_cap {
+  double max_util;          /* Umax = max_a load[a] / cap[a] */
+  int64_t argmax_arc;       /* lowest link id whose utilisation equals max_util */
+  double min_util;
+  int64_t sum_dist;         /* as passed in */
+  int64_t n_links;          /* E */
+  int32_t n_nodes;          /* N */
+  int32_t reserved;
+  double total_capacity;    /* sum_a cap[a] */
+  double max_node_capacity; /* largest sum of cap over the out-links of one node */
+  double t_sched;           /* Umax * m / b */
+  double t_lb_nd;           /* sum_dist * m / (N * max_node_capacity * b) */
+  double t_lb_links;        /* sum_dist * m / (total_capacity * b) */
+  double ratio;             /* t_sched / t_lb_nd */
+  double throughput;        /* (N-1) * m / t_sched (Sec. 2.2) */
+  double flow_value;        /* f = 1 / Umax */
+  double throughput_upper;  /* (N-1) * f * b (Sec. 5.1) */
+} a2a_bound_cap;
+int a2a_schedule_bound_cap(const a2a_topo* topo, const double* load, const double* cap, int64_t sum_dist,
+                           int64_t flags, double m_bytes, double b_bytes_per_s, a2a_bound_cap* out,
+                           void* hip_stream);
+
+/*
  * Lower bound of Theorem 1 (Sec. 5.4) for any topology with N hosts and out-degree d: a source
  * reaches at most d^l hosts in l hops, so sum_t D(r,t) >= S_min(N,d), the distance sum of the
  * arborescence that fills level l with d^l hosts until all N are placed, and by Eq. (lb) the

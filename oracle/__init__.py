@@ -11,7 +11,9 @@ from .binding import (  # noqa: F401
     build,
     run,
     bound,
+    bound_cap,
     tree_sum,
     OracleResult,
     BOUND_FIELDS,
+    CAP_FIELDS,
 )

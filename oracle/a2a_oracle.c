@@ -24,7 +24,7 @@
  * when it is visited).  Threads only split the source range; each owns a private
  * load vector and the vectors are merged in thread order.
  *
- * Pins (tests/test_oracle_*.py): torus / hypercube / K4,4 closed forms, the
+ * Pins (tests/test_oracle_*.py, tests/test_capacities.py): torus / hypercube / K4,4 closed forms, the
  * 3x3x3-torus flow value 1/9 of Sec. 5.1, flow-conservation and level-cut
  * invariants, exact brute-force path enumeration for N <= 12.
  */
@@ -237,6 +237,64 @@ int a2a_oracle_bound(int32_t N, const int32_t* row_ptr, const double* load, int6
   out[7] = (double)(N - 1) * m / out[3];
   out[8] = 1.0 / lmax;
   out[9] = (double)(N - 1) * out[8] * b;
+  return 0;
+}
+
+/*
+ * The same figures for a network G = (V, E, cap) with link capacities (Sec. 3.1.1): the flows of
+ * a routing fit when every link's load, scaled by the common rate, stays within its capacity,
+ * so the all-to-all time of the routing is the largest load / cap over the links (Sec. 5.3 with
+ * unit capacities).  cap[a] multiplies the bandwidth b of a unit link.  out[] (12 doubles):
+ *  0 max utilisation Umax = max_a load[a] / cap[a]
+ *  1 lowest link id attaining it
+ *  2 min utilisation
+ *  3 t_sched    = Umax * m / b
+ *  4 t_lb_nd    = sumD * m / (N * cmax * b), cmax = largest total out-capacity of a node
+ *                 (Eq. (lb) with "d x N" read as the capacity N nodes of that out-capacity have)
+ *  5 t_lb_links = sumD * m / (sum_a cap[a] * b)   (demand sum D against the true total capacity)
+ *  6 ratio      = t_sched / t_lb_nd
+ *  7 throughput = (N-1) m / t_sched
+ *  8 f          = 1 / Umax
+ *  9 upper      = (N-1) f b
+ * 10 sum_a cap[a]
+ * 11 cmax
+ * Returns -2 if some capacity is not a positive finite number.
+ */
+int a2a_oracle_bound_cap(int32_t N, const int32_t* row_ptr, const double* load, const double* cap,
+                         int64_t sum_dist, double m, double b, double* out) {
+  if (N <= 0 || !row_ptr || !out) return -1;
+  int64_t E = row_ptr[N];
+  if (E <= 0 || !load || !cap) return -1;
+  for (int64_t a = 0; a < E; ++a)
+    if (!(cap[a] > 0.0) || cap[a] > 1.7976931348623157e308) return -2;
+  double umax = load[0] / cap[0], umin = umax, total = 0.0, cmax = 0.0;
+  int64_t arg = 0;
+  for (int32_t u = 0; u < N; ++u) {
+    double node_cap = 0.0;
+    for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) {
+      double util = load[a] / cap[a];
+      if (util > umax) {
+        umax = util;
+        arg = a;
+      }
+      if (util < umin) umin = util;
+      node_cap += cap[a];
+      total += cap[a];
+    }
+    if (node_cap > cmax) cmax = node_cap;
+  }
+  out[0] = umax;
+  out[1] = (double)arg;
+  out[2] = umin;
+  out[3] = umax * m / b;
+  out[4] = (double)sum_dist * m / ((double)N * cmax * b);
+  out[5] = (double)sum_dist * m / (total * b);
+  out[6] = out[3] / out[4];
+  out[7] = (double)(N - 1) * m / out[3];
+  out[8] = 1.0 / umax;
+  out[9] = (double)(N - 1) * out[8] * b;
+  out[10] = total;
+  out[11] = cmax;
   return 0;
 }
 

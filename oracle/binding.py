@@ -47,6 +47,10 @@ def _load():
         lib.a2a_oracle_bound.argtypes = [
             ctypes.c_int32, i32p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_double,
             ctypes.c_double, ctypes.c_void_p]
+        lib.a2a_oracle_bound_cap.restype = ctypes.c_int
+        lib.a2a_oracle_bound_cap.argtypes = [
+            ctypes.c_int32, i32p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_double,
+            ctypes.c_double, ctypes.c_void_p]
         lib.a2a_oracle_tree_sum.restype = ctypes.c_int64
         lib.a2a_oracle_tree_sum.argtypes = [ctypes.c_int32, ctypes.c_int32]
         _lib = lib
@@ -107,6 +111,27 @@ def bound(row_ptr, load, sum_dist: int, m: float = 1.0, b: float = 1.0) -> dict:
     if rc != 0:
         raise ValueError("a2a_oracle_bound rejected its arguments")
     res = dict(zip(BOUND_FIELDS, out.tolist()))
+    res["argmax_arc"] = int(res["argmax_arc"])
+    return res
+
+
+CAP_FIELDS = BOUND_FIELDS + ("total_capacity", "max_node_capacity")
+
+
+def bound_cap(row_ptr, load, cap, sum_dist: int, m: float = 1.0, b: float = 1.0) -> dict:
+    """Schedule figures with link capacities; ValueError for a capacity that is not positive."""
+    lib = _load()
+    row_ptr, rp = _i32(row_ptr)
+    load = np.ascontiguousarray(load, dtype=np.float64)
+    cap = np.ascontiguousarray(cap, dtype=np.float64)
+    if len(cap) != len(load):
+        raise ValueError("cap and load differ in length")
+    out = np.zeros(len(CAP_FIELDS), dtype=np.float64)
+    rc = lib.a2a_oracle_bound_cap(len(row_ptr) - 1, rp, load.ctypes.data, cap.ctypes.data, int(sum_dist),
+                                  float(m), float(b), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("a2a_oracle_bound_cap rejected its arguments (%d)" % rc)
+    res = dict(zip(CAP_FIELDS, out.tolist()))
     res["argmax_arc"] = int(res["argmax_arc"])
     return res
 

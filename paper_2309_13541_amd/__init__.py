@@ -7,6 +7,7 @@ package does not load the library; the first call does, and fails loudly if it i
 from .binding import (  # noqa: F401
     A2AError,
     Bound,
+    BoundCap,
     Profile,
     PROF_KERNELS,
     Topology,

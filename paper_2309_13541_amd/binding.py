@@ -38,7 +38,7 @@ FLAG_UNREACHABLE = 0x2
 EXPORTED_SYMBOLS = (
     "a2a_topo_create", "a2a_topo_destroy", "a2a_topo_info", "a2a_workspace_bytes",
     "a2a_distances", "a2a_link_loads", "a2a_schedule_bound", "a2a_status_string",
-    "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound",
+    "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound", "a2a_schedule_bound_cap",
 )
 
 PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_few", "bwd_rows", "bwd_init", "bwd_few",
@@ -69,6 +69,21 @@ class Bound(ctypes.Structure):
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class BoundCap(ctypes.Structure):
+    """Mirror of ``a2a_bound_cap``."""
+    _fields_ = [
+        ("max_util", ctypes.c_double), ("argmax_arc", ctypes.c_int64), ("min_util", ctypes.c_double),
+        ("sum_dist", ctypes.c_int64), ("n_links", ctypes.c_int64), ("n_nodes", ctypes.c_int32),
+        ("reserved", ctypes.c_int32), ("total_capacity", ctypes.c_double),
+        ("max_node_capacity", ctypes.c_double), ("t_sched", ctypes.c_double), ("t_lb_nd", ctypes.c_double),
+        ("t_lb_links", ctypes.c_double), ("ratio", ctypes.c_double), ("throughput", ctypes.c_double),
+        ("flow_value", ctypes.c_double), ("throughput_upper", ctypes.c_double),
+    ]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
 
 
 class TreeBound(ctypes.Structure):
@@ -140,6 +155,8 @@ def load_library():
     lib.a2a_distances.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.a2a_link_loads.restype = ctypes.c_int
     lib.a2a_link_loads.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.a2a_schedule_bound_cap.restype = ctypes.c_int
+    lib.a2a_schedule_bound_cap.argtypes = [vp, vp, vp, i64, i64, ctypes.c_double, ctypes.c_double, vp, vp]
     lib.a2a_schedule_bound.restype = ctypes.c_int
     lib.a2a_schedule_bound.argtypes = [vp, vp, i64, i64, ctypes.c_double, ctypes.c_double,
                                        ctypes.POINTER(Bound), vp]
@@ -248,4 +265,13 @@ class Topology:
                                                float(m_bytes), float(b_bytes_per_s), ctypes.byref(out),
                                                _stream(stream))
         _check(st, "a2a_schedule_bound", allow=(ERR_DISCONNECTED,) if allow_disconnected else ())
+        return out, st
+
+    def schedule_bound_cap(self, load, cap, sum_dist: int, flags: int = 0, m_bytes: float = 1.0,
+                           b_bytes_per_s: float = 1.0, stream=None, allow_disconnected: bool = False):
+        out = BoundCap()
+        st = load_library().a2a_schedule_bound_cap(self._h, _ptr(load), _ptr(cap), int(sum_dist), int(flags),
+                                                   float(m_bytes), float(b_bytes_per_s), ctypes.byref(out),
+                                                   _stream(stream))
+        _check(st, "a2a_schedule_bound_cap", allow=(ERR_DISCONNECTED,) if allow_disconnected else ())
         return out, st

@@ -1181,4 +1181,69 @@ k_load_extrema(const double* __restrict__ load, long long E, long long* __restri
   }
 }
 
+// The same with link capacities (Sec. 3.1.1): utilisation load[a] / cap[a] instead of load[a];
+// also the total capacity (sum over links in link order, block by block: a fixed order) and the
+// largest total out-capacity of a node.  out[0..2] as k_load_extrema, out[3] = sum of cap,
+// out[4] = largest node capacity, out[5] = 1 if some capacity is not a positive finite number.
+// One workgroup; thread t takes nodes t, t + 1024, ... with their out-links.
+__global__ void __launch_bounds__(1024)
+k_util_extrema(const int32_t* __restrict__ out_ptr, const double* __restrict__ load,
+               const double* __restrict__ cap, int N, long long* __restrict__ out) {
+  __shared__ double s_max[1024], s_min[1024], s_sum[1024], s_cap[1024];
+  __shared__ long long s_arg[1024];
+  __shared__ int s_bad;
+  const int t = (int)threadIdx.x;
+  if (t == 0) s_bad = 0;
+  __syncthreads();
+  double mx = -1.0, mn = __builtin_huge_val(), sum = 0.0, cmax = 0.0;
+  long long arg = -1;
+  bool bad = false;
+  for (int u = t; u < N; u += 1024) {
+    double node_cap = 0.0;
+    const int p1 = out_ptr[u + 1];
+    for (int a = out_ptr[u]; a < p1; ++a) {
+      const double c = cap[a];
+      if (!(c > 0.0) || c > 1.7976931348623157e308) bad = true;
+      const double x = load[a] / c;
+      if (x > mx) {
+        mx = x;
+        arg = a;
+      }
+      if (x < mn) mn = x;
+      node_cap += c;
+    }
+    sum += node_cap;
+    if (node_cap > cmax) cmax = node_cap;
+  }
+  if (bad) s_bad = 1;
+  s_max[t] = mx;
+  s_min[t] = mn;
+  s_arg[t] = arg;
+  s_sum[t] = sum;
+  s_cap[t] = cmax;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (t < o) {
+      const double om = s_max[t + o];
+      const long long oa = s_arg[t + o];
+      if (oa >= 0 && (s_arg[t] < 0 || om > s_max[t] || (om == s_max[t] && oa < s_arg[t]))) {
+        s_max[t] = om;
+        s_arg[t] = oa;
+      }
+      if (s_min[t + o] < s_min[t]) s_min[t] = s_min[t + o];
+      s_sum[t] += s_sum[t + o];
+      if (s_cap[t + o] > s_cap[t]) s_cap[t] = s_cap[t + o];
+    }
+    __syncthreads();
+  }
+  if (t == 0) {
+    out[0] = __double_as_longlong(s_max[0]);
+    out[1] = s_arg[0];
+    out[2] = __double_as_longlong(s_min[0]);
+    out[3] = __double_as_longlong(s_sum[0]);
+    out[4] = __double_as_longlong(s_cap[0]);
+    out[5] = s_bad;
+  }
+}
+
 }  // namespace a2a_dev

@@ -628,6 +628,41 @@ int a2a_schedule_bound(const a2a_topo* t, const double* load, int64_t sum_dist, 
   return (flags & A2A_FLAG_UNREACHABLE) ? A2A_ERR_DISCONNECTED : A2A_OK;
 }
 
+int a2a_schedule_bound_cap(const a2a_topo* t, const double* load, const double* cap, int64_t sum_dist,
+                           int64_t flags, double m_bytes, double b_bytes_per_s, a2a_bound_cap* out,
+                           void* hip_stream) {
+  if (!t || !out || !load || !cap || t->E <= 0 || !(m_bytes > 0.0) || !(b_bytes_per_s > 0.0) || sum_dist < 0)
+    return A2A_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  k_util_extrema<<<1, 1024, 0, st>>>(t->d_out_ptr, load, cap, t->N, (long long*)t->d_small);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(t->h_pinned, t->d_small, 6 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (t->h_pinned[5] != 0) return A2A_ERR_INVALID_ARG;  // a capacity that is not positive and finite
+  double umax, umin, total, cmax;
+  std::memcpy(&umax, &t->h_pinned[0], 8);
+  std::memcpy(&umin, &t->h_pinned[2], 8);
+  std::memcpy(&total, &t->h_pinned[3], 8);
+  std::memcpy(&cmax, &t->h_pinned[4], 8);
+  const double m = m_bytes, b = b_bytes_per_s;
+  out->max_util = umax;
+  out->argmax_arc = t->h_pinned[1];
+  out->min_util = umin;
+  out->sum_dist = sum_dist;
+  out->n_links = t->E;
+  out->n_nodes = t->N;
+  out->total_capacity = total;
+  out->max_node_capacity = cmax;
+  out->t_sched = umax * m / b;
+  out->t_lb_nd = (double)sum_dist * m / ((double)t->N * cmax * b);
+  out->t_lb_links = (double)sum_dist * m / (total * b);
+  out->ratio = out->t_sched / out->t_lb_nd;
+  out->throughput = (double)(t->N - 1) * m / out->t_sched;
+  out->flow_value = 1.0 / umax;
+  out->throughput_upper = (double)(t->N - 1) * out->flow_value * b;
+  return (flags & A2A_FLAG_UNREACHABLE) ? A2A_ERR_DISCONNECTED : A2A_OK;
+}
+
 int a2a_tree_lower_bound(int32_t N, int32_t d, double m_bytes, double b_bytes_per_s, a2a_tree_bound* out) {
   if (!out || N < 1 || d < 1 || !(m_bytes > 0.0) || !(b_bytes_per_s > 0.0)) return A2A_ERR_INVALID_ARG;
   int64_t left = (int64_t)N - 1, width = 1, sum = 0;

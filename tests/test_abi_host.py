@@ -84,6 +84,9 @@ def test_null_handles_are_rejected(a2a):
     assert lib.a2a_link_loads(None, 0, 1, None, None, None, None, 0, None) == a2a.ERR_INVALID_ARG
     out = a2a.Bound()
     assert lib.a2a_schedule_bound(None, None, 0, 0, 1.0, 1.0, ctypes.byref(out), None) == a2a.ERR_INVALID_ARG
+    outc = a2a.BoundCap()
+    assert lib.a2a_schedule_bound_cap(None, None, None, 0, 0, 1.0, 1.0, ctypes.byref(outc),
+                                      None) == a2a.ERR_INVALID_ARG
     lib.a2a_topo_destroy(None)
 
 
@@ -94,3 +97,8 @@ def test_bound_struct_matches_header(a2a):
     fields = re.findall(r"\b(?:double|int64_t|int32_t)\s+([a-z_]+);", body)
     assert fields == [n for n, _ in a2a.Bound._fields_]
     assert ctypes.sizeof(a2a.Bound) == 8 * 13
+    body = re.search(r"typedef struct a2a_bound_cap \{(.*?)\} a2a_bound_cap;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(?:double|int64_t|int32_t)\s+([a-z_]+);", body)
+    assert fields == [n for n, _ in a2a.BoundCap._fields_]
+    assert ctypes.sizeof(a2a.BoundCap) == 8 * 15
