@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--cpu-sources", type=int, default=None,
                     help="sources in the oracle's timed sample (default: sized for ~10-20 s)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-distances", action="store_true",
+                    help="skip the a2a_distances leg (distance matrix only, reported beside the metric)")
     ap.add_argument("--max-workspace-gib", type=float, default=None)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 "
@@ -177,6 +179,39 @@ def main():
         "per_kernel": per_kernel,
     }
 
+    # a2a_distances alone (BFS + the int32 distance matrix), reported beside the metric
+    dist_leg = None
+    ws_gib = ws.numel() / 2 ** 30
+    if not args.no_distances:
+        del ws
+        torch.cuda.empty_cache()
+        wsd = topo.alloc_workspace(N, a2a.WS_DISTANCES, cap)
+        dist = torch.empty((N, N), dtype=torch.int32, device="cuda")
+        dsrc = torch.empty(N, dtype=torch.int64, device="cuda")
+        unr = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+        def dstep():
+            topo.distances(0, N, dist=dist, sigma=None, dist_sum=dsrc, unreachable=unr, flags=None, workspace=wsd)
+
+        dstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dstep()
+        torch.cuda.synchronize()
+        dsec = (time.perf_counter() - t0) / args.steps
+        topo.profile_enable(1)
+        dstep()
+        dprof = topo.profile_read()
+        topo.profile_enable(0)
+        if fl == 0:
+            assert int(dsrc.sum().item()) == sum_dist and int(unr.item()) == 0
+        dist_leg = {"ms_per_step": dsec * 1e3, "teps_bfs": N * E / dsec, "unit": "edges/s",
+                    "alg_bytes": 4.0 * N * N, "frac": 4.0 * N * N / dsec / 1e9 / HBM_PEAK_GBPS,
+                    "kernel_ms": {k: round(dprof[k]["ms"], 3) for k in ("init", "bfs", "extract")},
+                    "what": "a2a_distances over all sources: BFS + int32 dist[N][N] + per-source sums"}
+        del dist, wsd
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -206,12 +241,13 @@ def main():
             "C1": "8x8 torus", "C2": "hypercube n=10", "C3": "16x16x16 torus",
             "C4": "Imase-Itoh N=16384 d=4", "C5": "random 8-regular digraph N=65536 seed 1234",
         }[args.config] + ", unit all-pairs demand", "N": N, "E": E, "sources": N,
-            "workspace_GiB": ws.numel() / 2 ** 30, "groups_per_step": prof["groups"] // timed_calls,
+            "workspace_GiB": ws_gib, "groups_per_step": prof["groups"] // timed_calls,
             "depth": prof["depth"], "dag_links": dag},
         "result": {"sum_dist": sum_dist, "max_load": bound.max_load, "argmax_arc": bound.argmax_arc,
                    "ratio_to_lower_bound": bound.ratio, "flags": fl},
         "topo_create_ms": t_create * 1e3,
         "roofline": roofline,
+        "distances": dist_leg,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

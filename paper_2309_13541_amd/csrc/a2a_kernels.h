@@ -1027,7 +1027,7 @@ k_reduce_part(const double* __restrict__ part, size_t Epad, int G, long long E, 
 // ---------------------------------------------------------------------------------------
 
 // dist[s][v] from the level masks, through a 64 x 64 LDS tile so that rows of dist are written
-// with consecutive lanes on consecutive nodes.  One wave per (batch, 64-node tile).
+// with consecutive lanes on consecutive nodes.  One wave per (batch, 64-node tile).  Any depth.
 __global__ void __launch_bounds__(kWave)
 k_extract_dist(GroupView gv, int tiles, int depth, int32_t* __restrict__ dist,
                long long* __restrict__ dist_sum) {
@@ -1060,6 +1060,58 @@ k_extract_dist(GroupView gv, int tiles, int depth, int32_t* __restrict__ dist,
     }
     if (s) atomicAdd((unsigned long long*)&dist_sum[row0 + t], (unsigned long long)s);
   }
+}
+
+// The same for depth < 256 without the LDS tile: a thread per node first folds the level masks into
+// bit planes (plane k = OR of the masks of the levels whose bit k is set), so that the distance of
+// source j is read off bit j of the planes; the wave then goes through the sources together (j is
+// wave-uniform: no divergence), every lane writing its node's entry of row j.  The per-source sums
+// come from ballots: bit k of the distances of source j over the wave's nodes is one popcount.
+// `planes` = number of bits of `depth`.
+__global__ void __launch_bounds__(kBlock)
+k_extract_dist_planes(GroupView gv, int depth, int planes, int32_t* __restrict__ dist,
+                      long long* __restrict__ dist_sum) {
+  // The masks of the kSub batches of a super-batch share memory lines (64 bytes per node): their
+  // workgroups for the same node block are neighbours in launch order and run on the same XCD, so
+  // that the lines are fetched once and found in that XCD's L2 by the other seven.
+  const unsigned i = blockIdx.x / kXcd;  // position in the XCD's own sequence of workgroups
+  const int k = (int)(i % kSub);
+  const int nblk = (int)((i / kSub) % (unsigned)gv.bpb);
+  const int sb = (int)(i / kSub / (unsigned)gv.bpb) * kXcd + (int)(blockIdx.x % kXcd);
+  const int g = sb * kSub + k;
+  if (g >= gv.G) return;
+  const int v = nblk * kBlock + (int)threadIdx.x;  // < Npad: the mask arrays are padded with zeros
+  const int lane = lane_id();
+  uint64_t B[8], R = 0;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) B[p] = 0;
+  for (int l = 0; l <= depth; ++l) {
+    const uint64_t m = gv.bm[bm_at(gv, sb, l, v, k)];
+    R |= m;
+#pragma unroll
+    for (int p = 0; p < 8; ++p)
+      if ((l >> p) & 1) B[p] |= m;
+  }
+  const int row0 = (gv.batch0 + g) * 64;
+  const int cnt = min(64, gv.src_count - row0);
+  const bool live = v < gv.N;
+  long long mine = 0;  // lane j: distance sum of source j over this wave's nodes
+  for (int j = 0; j < cnt; ++j) {
+    int d = 0;
+    long long s = 0;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      if (p < planes) {
+        const int bit = (int)((B[p] >> j) & 1ull);
+        d |= bit << p;
+        if (dist_sum != nullptr) s += (long long)__popcll(__ballot(bit != 0 && live)) << p;
+      }
+    }
+    if (dist != nullptr && live) dist[(size_t)(row0 + j) * gv.N + v] = ((R >> j) & 1ull) ? d : -1;
+    if (lane == j) mine = s;
+  }
+  if (dist_sum != nullptr && lane < cnt && mine != 0)
+    atomicAdd((unsigned long long*)&dist_sum[row0 + lane], (unsigned long long)mine);
 }
 
 // sigma[s][v] from the level-compact rows, transposed through LDS.  One wave per tile.

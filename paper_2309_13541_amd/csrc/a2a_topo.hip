@@ -520,7 +520,14 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
     }
     if (dist || dist_sum) {
       ProfScope ps(t, PROF_EXTRACT, st);
-      k_extract_dist<<<grid_for(gv.G, tiles), kWave, 0, st>>>(gv, tiles, depth, dist, (long long*)dist_sum);
+      if (depth < 256) {
+        int planes = 0;
+        while ((depth >> planes) != 0) ++planes;
+        k_extract_dist_planes<<<grid_for(gv.SB, L.bpb * kSub), kBlock, 0, st>>>(gv, depth, planes, dist,
+                                                                                (long long*)dist_sum);
+      } else {
+        k_extract_dist<<<grid_for(gv.G, tiles), kWave, 0, st>>>(gv, tiles, depth, dist, (long long*)dist_sum);
+      }
     }
     rc = run_fold(r, gv, depth);
     if (rc != A2A_OK) return rc;

@@ -26,6 +26,9 @@ SMALL.update({
     "torus3x3x3": gen.torus([3, 3, 3]),
     "ring_odd_131": gen.ring(131),              # diameter 130, N not a multiple of 64
     "biring_200": gen.bidirectional_ring(200),  # diameter 100 = N/2
+    "ring_255": gen.ring(255),                  # diameter 254
+    "ring_256": gen.ring(256),                  # diameter 255: deepest that the bit-plane distance output takes
+    "ring_300": gen.ring(300),
     "kautz_81_8": gen.imase_itoh(81, 8),
     "kautz_100_3": gen.imase_itoh(100, 3),
     "rr_300_4": gen.random_regular(300, 4, 5),
