@@ -21,7 +21,7 @@ HBM_PEAK_GBPS = 8000.0
 
 
 KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd_level",
-               "fwd_few": "k_fwd_few", "bwd_rows": "k_bwd_level", "bwd_init": "k_bwd_init_level",
+               "fwd_few": "k_fwd_few", "bwd_rows": "k_bwd_level",
                "bwd_few": "k_bwd_few", "reduce": "k_reduce_part"}
 
 
@@ -58,11 +58,9 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
             continue
         if ran["bwd_few"][l]:
             out["bwd_few"] += links
-        if ran["bwd_init"][l]:
-            out["bwd_init"] += own
-        elif ran["bwd_few"][l] and fwd != "fwd_rows":  # few sources per node: the kernel writes coef itself
+        if ran["bwd_few"][l] and fwd != "fwd_rows":  # few sources per node: the kernel writes coef itself
             out["bwd_few"] += own
-        elif fwd:                                      # the forward launch left 1/sigma in coef
+        elif fwd:                                    # the forward launch left 1/sigma in coef
             out[fwd] += own
     out["reduce"] = 8.0 * nb * E
     return out

@@ -224,7 +224,6 @@ typedef enum a2a_prof_kernel {
   A2A_K_FWD_ROWS,  /* forward level, one wave per node (well-filled level) */
   A2A_K_FWD_FEW,   /* forward level with few sources per node: lanes = (node, link) or (node, source) */
   A2A_K_BWD_ROWS,  /* backward level, one wave per node */
-  A2A_K_BWD_INIT,  /* coef = 1/sigma sweep over a level (deepest level; before some A2A_K_BWD_FEW) */
   A2A_K_BWD_FEW,   /* backward level, lanes = (node, link) or (node, source) */
   A2A_K_REDUCE,    /* ordered sum of the per-batch link loads */
   A2A_K_EXTRACT,   /* dist / sigma output of a2a_distances */

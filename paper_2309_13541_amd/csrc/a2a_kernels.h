@@ -994,23 +994,6 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
   }
 }
 
-// coef = 1/sigma for every entry of a level (a flat sweep over the level's slice of the compact
-// arrays): level 0, when the forward pass did not run and could not leave it there.
-__global__ void __launch_bounds__(kBfsBlock) k_bwd_init_level(GroupView gv, int level) {
-  int sb, nblk;
-  if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
-  const int g = sb * kSub + (int)threadIdx.x / kWave;  // wave k sweeps batch k's slice
-  if (g >= gv.G) return;
-  const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
-  long long base = 0;
-  for (int l = 0; l < level; ++l) base += lt[l];
-  const long long cnt = lt[level];
-  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64 + base;
-  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64 + base;
-  for (long long e = (long long)nblk * kWave + lane_id(); e < cnt; e += (long long)gv.nb64 * kWave)
-    cf[e] = recip(dat[e]);
-}
-
 // load[a] = (first group ? 0 : load[a]) + part[0][a] + part[1][a] + ... in that order.
 __global__ void __launch_bounds__(kBlock)
 k_reduce_part(const double* __restrict__ part, size_t Epad, int G, long long E, int first,

@@ -52,7 +52,7 @@ namespace {
 
 enum {
   PROF_INIT = A2A_K_INIT, PROF_BFS = A2A_K_BFS, PROF_OFFSETS = A2A_K_OFFSETS, PROF_FWD = A2A_K_FWD_ROWS,
-  PROF_FWD_FEW = A2A_K_FWD_FEW, PROF_BWD = A2A_K_BWD_ROWS, PROF_BWD_INIT = A2A_K_BWD_INIT,
+  PROF_FWD_FEW = A2A_K_FWD_FEW, PROF_BWD = A2A_K_BWD_ROWS,
   PROF_BWD_FEW = A2A_K_BWD_FEW, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
   PROF_CLASSES = A2A_K_COUNT
 };
@@ -232,9 +232,10 @@ struct Run {
     return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kFewLanes;
   }
   bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
-  // Backward level that starts from coef = 1/sigma and only visits the sources with a successor.
+  // Backward level that starts from coef = 1/sigma (left there by the forward launch of that level)
+  // and only visits the sources with a successor; the deepest level needs no visit at all.
   bool coef_from_forward(int level, int depth) const {
-    return level == depth || (!few(level) && with_successors(level) < kFewLanes);
+    return level == depth || (level > 0 && !few(level) && with_successors(level) < kFewLanes);
   }
   // Expected number of sources of a node on level l that have a successor on level l+1.
   double with_successors(int l) const {
@@ -573,13 +574,8 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (t->E > 0) {
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
-      for (int l = depth; l >= 0; --l) {
+      for (int l = depth - 1; l >= 0; --l) {
         const bool adds = r.coef_from_forward(l, depth);
-        if (adds && l == 0) {  // no forward launch for level 0: every source is depth 0 (no links)
-          ProfScope ps(t, PROF_BWD_INIT, st, l);
-          k_bwd_init_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, st>>>(gv, l);
-        }
-        if (l == depth) continue;
         ProfScope ps(t, adds || r.few(l) ? PROF_BWD_FEW : PROF_BWD, st, l);
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
         if (adds)

@@ -288,3 +288,47 @@ def test_disabled_links_and_hosts(a2a, oracle):
             assert dtot == int(o.dist_sum.sum()) and lflags == o.flags
             assert_loads_close(load, o.load)
             topo.close()
+
+
+def _flavours(a2a, rp, col):
+    """Which kernel flavour each level got, read off the per-level launch times."""
+    import torch
+    topo = a2a.Topology(rp, col)
+    ws = topo.alloc_workspace(topo.N, a2a.WS_LOADS)
+    load = torch.empty(max(topo.E, 1), dtype=torch.float64, device="cuda")
+    topo.profile_enable(1)
+    topo.link_loads(0, topo.N, load=load, workspace=ws)
+    p = topo.profile_read()
+    topo.profile_enable(0)
+    nb = (topo.N + 63) // 64
+    seen = set()
+    for l in range(min(p["depth"] + 1, 63)):  # the profile keeps 64 levels, the last one a catch-all
+        lanes = p["pairs_level"][l] / (nb * topo.N)
+        ran = {k: p[k]["ms_level"][l] > 0 for k in ("fwd_rows", "fwd_few", "bwd_rows", "bwd_few")}
+        layout = "_node_source" if lanes >= 2.0 else "_node_link"
+        if ran["fwd_rows"]:
+            seen.add("fwd_rows")
+        if ran["fwd_few"]:
+            seen.add("fwd_few" + layout)
+        if ran["bwd_rows"]:
+            seen.add("bwd_rows")
+        if ran["bwd_few"]:
+            seen.add("bwd_add_only" if ran["fwd_rows"] else "bwd_few" + layout)
+    return seen
+
+
+def test_parity_set_reaches_every_kernel_flavour(a2a):
+    """The level kernels come in flavours picked from how full a level is; the graphs of
+    test_small_graphs_everything must between them run every one (else parity says nothing
+    about the ones left out)."""
+    seen = set()
+    for name in sorted(SMALL):
+        rp, col = SMALL[name]
+        if len(col) == 0:
+            continue
+        got = _flavours(a2a, rp, col)
+        print(name, sorted(got), flush=True)
+        seen |= got
+    want = {"fwd_rows", "fwd_few_node_link", "fwd_few_node_source", "bwd_rows", "bwd_few_node_link",
+            "bwd_few_node_source", "bwd_add_only"}
+    assert want <= seen, want - seen
