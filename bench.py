@@ -21,7 +21,7 @@ HBM_PEAK_GBPS = 8000.0
 
 
 KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd_level",
-               "fwd_few": "k_fwd_few", "bwd_rows": "k_bwd_level",
+               "fwd_few": "k_fwd_few", "fwd_spread": "k_fwd_spread", "bwd_rows": "k_bwd_level",
                "bwd_few": "k_bwd_few", "reduce": "k_reduce_part"}
 
 
@@ -48,7 +48,7 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
     for l in range(L):
         if ran["bfs"][l]:
             out["bfs"] += 1 * pairs[l]
-        fwd = next((k for k in ("fwd_rows", "fwd_few") if ran[k][l]), None)
+        fwd = next((k for k in ("fwd_rows", "fwd_few", "fwd_spread") if ran[k][l]), None)
         if fwd:
             out[fwd] += (1 + 8) * pairs[l] + 8 * dag_in[l]
         own = (8 + 8) * pairs[l]                      # sigma read + coef written at the node itself
@@ -58,7 +58,7 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
             continue
         if ran["bwd_few"][l]:
             out["bwd_few"] += links
-        if ran["bwd_few"][l] and fwd != "fwd_rows":  # few sources per node: the kernel writes coef itself
+        if ran["bwd_few"][l] and fwd in (None, "fwd_few"):  # few sources per node: the kernel writes coef itself
             out["bwd_few"] += own
         elif fwd:                                    # the forward launch left 1/sigma in coef
             out[fwd] += own

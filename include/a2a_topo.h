@@ -223,6 +223,7 @@ typedef enum a2a_prof_kernel {
   A2A_K_OFFSETS,   /* row offsets of the level-compact arrays */
   A2A_K_FWD_ROWS,  /* forward level, one wave per node (well-filled level) */
   A2A_K_FWD_FEW,   /* forward level with few sources per node: lanes = (node, link) or (node, source) */
+  A2A_K_FWD_SPREAD, /* forward level, many sources per node, short rows on the level before */
   A2A_K_BWD_ROWS,  /* backward level, one wave per node */
   A2A_K_BWD_FEW,   /* backward level, lanes = (node, link) or (node, source) */
   A2A_K_REDUCE,    /* ordered sum of the per-batch link loads */

@@ -940,6 +940,115 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
   }
 }
 
+// --- forward level whose in-neighbours' rows are short: lane = (node, link), whole rows --------
+//
+// Third use of the tile layout, for a level with many sources per node whose in-neighbours have
+// few: lane 8i+j reads the row of link j of node i from end to end (its entries are adjacent in
+// memory: one or two lines per link, one request per entry and 64 links at a time instead of one
+// request per link and node) and adds every entry whose source the node has on this level to the
+// node's accumulator for that source in LDS (atomic adds: path counts are whole numbers below
+// 2^53, so the order does not matter; beyond, the result is flagged as inexact anyway).  Then the
+// node's sources collect their sums, a lane per source, and write the node's row.
+
+// Adds the entries of this lane's link to acc[source] (the accumulators of this lane's node).
+__device__ __forceinline__ void spread_link(const double* __restrict__ rows, const Tile& tl, uint64_t mu,
+                                            double* __restrict__ acc) {
+  uint64_t rest = tl.mask;  // sources of the link's row, ascending = its entries in order
+  uint32_t e = tl.off;
+  while (__ballot(rest != 0) != 0) {  // eight entries per round, all requested first
+    const int c = __popcll(rest);
+    double x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      x[k] = 0.0;
+      if (k < c) x[k] = entry(rows, e + (uint32_t)k);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (rest != 0) {
+        const int s = __builtin_ctzll(rest);
+        rest &= rest - 1;
+        if ((mu >> s) & 1ull) unsafeAtomicAdd(&acc[s], x[k]);
+      }
+    }
+    e += 8;
+  }
+}
+
+template <bool kCountDag>
+__global__ void __launch_bounds__(kBlock)
+k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
+             bool init_coef, long long* __restrict__ misc) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int lane = lane_id();
+  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (v0 >= gv.N) return;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ prev = cur - gv.Npad;
+  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
+  __shared__ double s_acc[kWavesPerBlock][8][kWave];  // [node of the tile][source]
+  double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
+  const NodeIdx me = load_idx(cur + v0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
+  if (nodes_active == 0) return;
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (me.mask != 0) {
+    lr.p0 = in_ptr[v0 + lane];
+    lr.p1 = in_ptr[v0 + lane + 1];
+  }
+  bool inexact = false;
+  int dag = 0;
+  int q;
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
+  int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
+#pragma unroll 1
+  for (int c = 0; c < 8; ++c) {
+    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
+    nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i][lane] = 0.0;
+      __builtin_amdgcn_wave_barrier();
+      const int node = 8 * c + (lane >> 3);
+      const uint64_t mu = shfl64(me.mask, node);
+      spread_link(dat, tile, mu, acc[lane >> 3]);
+      if (kCountDag) dag += __popcll(tile.mask & mu);
+      // nodes with more than eight in-links: further tiles into the same accumulators
+      const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
+      for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
+        const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
+        spread_link(dat, extra, mu, acc[lane >> 3]);
+        if (kCountDag) dag += __popcll(extra.mask & mu);
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+      for (int i = 0; i < 8; ++i) {  // lane = source: the node's sums go to its row
+        const uint64_t newv = readlane64(me.mask, 8 * c + i);
+        if (newv == 0) continue;
+        const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+        if (lane_in(newv)) {
+          const double a = acc[i][lane];
+          const uint32_t e = of + rank_in(newv);
+          entry(dat, e) = a;
+          if (cf != nullptr) entry(cf, e) = recip(a);
+          inexact |= a >= kTwo53;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    tile = tile_next;
+  }
+  if (inexact) misc[0] = 1;
+  if (kCountDag) {
+    dag = wave_sum_int(dag);
+    if (dag != 0 && lane == 0)
+      atomicAdd((unsigned long long*)&gv.dag[(size_t)g * gv.Lcap + level], (unsigned long long)dag);
+  }
+}
+
 template <bool kSlots, bool kUnion>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {

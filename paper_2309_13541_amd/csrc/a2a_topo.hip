@@ -52,7 +52,7 @@ namespace {
 
 enum {
   PROF_INIT = A2A_K_INIT, PROF_BFS = A2A_K_BFS, PROF_OFFSETS = A2A_K_OFFSETS, PROF_FWD = A2A_K_FWD_ROWS,
-  PROF_FWD_FEW = A2A_K_FWD_FEW, PROF_BWD = A2A_K_BWD_ROWS,
+  PROF_FWD_FEW = A2A_K_FWD_FEW, PROF_FWD_SPREAD = A2A_K_FWD_SPREAD, PROF_BWD = A2A_K_BWD_ROWS,
   PROF_BWD_FEW = A2A_K_BWD_FEW, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
   PROF_CLASSES = A2A_K_COUNT
 };
@@ -211,9 +211,11 @@ int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
 // Which kernel flavour a level gets, from the average number of sources per node on it:
 // below kFewLanes the lanes of a wave stand for (node, link) or (node, source) pairs of eight
 // nodes (k_fwd_few / k_bwd_few), from kSlotLanes on in the (node, source) layout; above, one wave
-// per node with a lane per source (k_fwd_level / k_bwd_level).  A well-filled level whose nodes
-// have fewer than kFewLanes sources with a successor is swept with 1/sigma and then visited by
-// k_bwd_few for those sources only.
+// per node with a lane per source (k_fwd_level / k_bwd_level).  Two mixed cases: a forward level
+// above kFewLanes whose predecessor is below it reads whole rows, a lane per (node, link)
+// (k_fwd_spread); a backward level above kFewLanes whose nodes have fewer than kFewLanes sources
+// with a successor starts from the 1/sigma that the forward launch left in coef and is visited
+// by k_bwd_few for those sources only.
 constexpr double kFewLanes = 8.0;
 constexpr double kSlotLanes = 2.0;
 // Largest topology: a batch's value array (N * 64 entries of 8 bytes) is addressed with 32-bit
@@ -329,14 +331,18 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   }
   const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
-    ProfScope ps(t, r.few(l) ? PROF_FWD_FEW : PROF_FWD, r.st, l);
+    const bool few = r.few(l);
+    const bool spread = !few && r.few(l - 1);  // many sources per node here, few on the level before
+    ProfScope ps(t, few ? PROF_FWD_FEW : (spread ? PROF_FWD_SPREAD : PROF_FWD), r.st, l);
     const bool count = t->prof_mode == 2;
     // levels that the backward pass only adds to get coef = 1/sigma from the forward pass
     const bool init_coef = gv.coef != nullptr && r.coef_from_forward(l, depth);
     auto launch = [&](auto kernel) {
       kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
     };
-    if (!r.few(l))
+    if (spread)
+      count ? launch(k_fwd_spread<true>) : launch(k_fwd_spread<false>);
+    else if (!few)
       count ? launch(k_fwd_level<true>) : launch(k_fwd_level<false>);
     else if (r.slots(l))
       count ? launch(k_fwd_few<true, true>) : launch(k_fwd_few<false, true>);
