@@ -22,7 +22,7 @@ HBM_PEAK_GBPS = 8000.0
 
 KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd_level",
                "fwd_few": "k_fwd_few", "fwd_spread": "k_fwd_spread", "bwd_rows": "k_bwd_level",
-               "bwd_few": "k_bwd_few", "reduce": "k_reduce_part"}
+               "bwd_few": "k_bwd_few", "bwd_spread": "k_bwd_spread", "reduce": "k_reduce_part"}
 
 
 def algorithmic_bytes(prof, dag_level, nb, E, steps):
@@ -35,8 +35,8 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
     proportion to their links) + 8 B read (ordered reduction).
     A launch at level l is charged the pairs of level l and the links into (forward) or out of
     (backward) that level; which kernel class ran the level comes from the per-level timings.
-    Where the forward launch also leaves coef = 1/sigma behind (deepest level; well-filled
-    level with sparse successors), the node's own 16 backward bytes are charged to it.
+    The forward launch of the deepest level also leaves coef = 1/sigma behind (no backward
+    launch there): that level's own 16 backward bytes are charged to it.
     """
     L = len(prof["pairs_level"])
     pairs = [p / steps for p in prof["pairs_level"]]       # per step
@@ -53,14 +53,10 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
             out[fwd] += (1 + 8) * pairs[l] + 8 * dag_in[l]
         own = (8 + 8) * pairs[l]                      # sigma read + coef written at the node itself
         links = 8 * dag_out[l] + 8.0 * nb * E * dag_out[l] / dag_total
-        if ran["bwd_rows"][l]:
-            out["bwd_rows"] += own + links
-            continue
-        if ran["bwd_few"][l]:
-            out["bwd_few"] += links
-        if ran["bwd_few"][l] and fwd in (None, "fwd_few"):  # few sources per node: the kernel writes coef itself
-            out["bwd_few"] += own
-        elif fwd:                                    # the forward launch left 1/sigma in coef
+        bwd = next((k for k in ("bwd_rows", "bwd_few", "bwd_spread") if ran[k][l]), None)
+        if bwd:
+            out[bwd] += own + links
+        elif fwd:  # deepest level: the forward launch leaves coef = 1/sigma, nothing runs backward
             out[fwd] += own
     out["reduce"] = 8.0 * nb * E
     return out
@@ -137,9 +133,14 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = topo.profile_read()
-    # one more, untimed, step counts the (source, link) pairs on shortest paths
+    # one more, untimed, step counts the (source, link) pairs on shortest paths; its loads must be
+    # the same bits as the timed step's (fixed summation order)
+    load_timed = load.clone()
     topo.profile_enable(2)
     step()
+    torch.cuda.synchronize()
+    rerun_bitwise = bool(torch.equal(load_timed, load))
+    del load_timed
     prof2 = topo.profile_read()
     dag, dag_level = prof2["dag_links"], prof2["dag_level"]
     topo.profile_enable(0)
@@ -242,7 +243,7 @@ def main():
             "workspace_GiB": ws_gib, "groups_per_step": prof["groups"] // timed_calls,
             "depth": prof["depth"], "dag_links": dag},
         "result": {"sum_dist": sum_dist, "max_load": bound.max_load, "argmax_arc": bound.argmax_arc,
-                   "ratio_to_lower_bound": bound.ratio, "flags": fl},
+                   "rerun_bitwise": rerun_bitwise, "ratio_to_lower_bound": bound.ratio, "flags": fl},
         "topo_create_ms": t_create * 1e3,
         "roofline": roofline,
         "distances": dist_leg,

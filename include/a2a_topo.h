@@ -226,6 +226,7 @@ typedef enum a2a_prof_kernel {
   A2A_K_FWD_SPREAD, /* forward level, many sources per node, short rows on the level before */
   A2A_K_BWD_ROWS,  /* backward level, one wave per node */
   A2A_K_BWD_FEW,   /* backward level, lanes = (node, link) or (node, source) */
+  A2A_K_BWD_SPREAD, /* backward level, many sources per node, short rows on the level after */
   A2A_K_REDUCE,    /* ordered sum of the per-batch link loads */
   A2A_K_EXTRACT,   /* dist / sigma output of a2a_distances */
   A2A_K_COUNT

@@ -41,7 +41,7 @@ EXPORTED_SYMBOLS = (
     "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound", "a2a_schedule_bound_cap",
 )
 
-PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few",
+PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few", "bwd_spread",
                 "reduce", "extract")
 PROF_MAX_LEVELS = 64
 

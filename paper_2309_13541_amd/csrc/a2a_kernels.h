@@ -435,7 +435,7 @@ __device__ __forceinline__ int gather8(const double* __restrict__ rows, const Ti
 }
 
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
-// cf (may be null): the backward pass will only add to this level's coef, so 1/sigma goes there now.
+// cf (may be null): the deepest level's coef is just 1/sigma, which goes there now.
 __device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __restrict__ cf, const NodeIdx& me,
                                            int node, const double (&x)[8]) {
   double a = 0.0;
@@ -779,17 +779,6 @@ __device__ __forceinline__ uint64_t bcast8(uint64_t x) {
   return ((uint64_t)bcast8<kSrc>((uint32_t)(x >> 32)) << 32) | bcast8<kSrc>((uint32_t)x);
 }
 
-// OR over the eight lanes of a node; every one of them gets the result.
-__device__ __forceinline__ uint32_t or_links8(uint32_t x) {
-  x |= (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x141, 0xF, 0xF, true);  // row_half_mirror
-  x |= (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
-  x |= (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
-  return x;
-}
-__device__ __forceinline__ uint64_t or_links8(uint64_t x) {
-  return ((uint64_t)or_links8((uint32_t)(x >> 32)) << 32) | or_links8((uint32_t)x);
-}
-
 // Removes the next (up to) eight sources from `rest`; returns the k-th of them, -1 if none.
 __device__ __forceinline__ int slot_take8(uint64_t& rest, int k) {
   int mine = -1;
@@ -847,40 +836,31 @@ __device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, double* __res
   return big;
 }
 
-// Returns, in lane 8i+j, the load of link j of node i from this tile.  kUnion: the node's row
-// already holds 1/sigma and only the sources that some link of the tile carries are visited
-// (a well-filled level whose successors are sparse); their entries are then found by rank.
-template <bool kUnion>
+// Returns, in lane 8i+j, the load of link j of node i from this tile.
 __device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
                                            uint64_t mu, uint32_t ofu, bool add, int lane) {
-  uint64_t rest = kUnion ? or_links8(tl.mask & mu) : mu;
+  uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   double p[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = 0.0;
   while (__ballot(rest != 0) != 0) {
     const int s = slot_take8(rest, lane & 7);
-    if (kUnion) e = ofu + (s >= 0 ? below(mu, s) : 0u);
     double x[8];
     slot_fetch8(cf, tl, s, x);
-    double sg = 1.0, was = 1.0;
-    if (kUnion) {  // the row holds 1/sigma (plus earlier rounds): sigma from there, one read less
-      if (s >= 0) was = entry(cf, e);
-      sg = add ? (s >= 0 ? entry(dat, e) : 1.0) : recip(was);
-    } else if (s >= 0) {
-      sg = entry(dat, e);
-    }
+    double sg = 1.0;
+    if (s >= 0) sg = entry(dat, e);
     double a = 0.0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       a += x[j];
       p[j] = __builtin_fma(sg, x[j], p[j]);
     }
-    if (s >= 0 && !((add || kUnion) && a == 0.0)) {
-      a += kUnion ? was : (add ? entry(cf, e) : recip(sg));
+    if (s >= 0 && !(add && a == 0.0)) {
+      a += add ? entry(cf, e) : recip(sg);
       entry(cf, e) = a;
     }
-    if (!kUnion) e += 8;
+    e += 8;
   }
   return group_sum8(p, lane);
 }
@@ -1024,10 +1004,9 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
         if (kCountDag) dag += __popcll(extra.mask & mu);
       }
       __builtin_amdgcn_wave_barrier();
-#pragma unroll 1
+#pragma unroll
       for (int i = 0; i < 8; ++i) {  // lane = source: the node's sums go to its row
         const uint64_t newv = readlane64(me.mask, 8 * c + i);
-        if (newv == 0) continue;
         const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
         if (lane_in(newv)) {
           const double a = acc[i][lane];
@@ -1049,7 +1028,122 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
   }
 }
 
-template <bool kSlots, bool kUnion>
+// --- backward level whose successors' rows are short: the mirror image ----------------------
+//
+// A level with many sources per node whose successors have few: the node's sigma and 1/sigma go
+// to LDS (a lane per source), then lane 8i+j reads the coef row of link j of node i from end to
+// end, adds every entry whose source the node has on this level to the node's accumulator for
+// that source and, times the node's sigma, to the link's load (lane-local, in row order); then
+// the accumulators go to the node's coef row, a lane per source.  The accumulators are private to
+// the wave and start at zero: one or two contributions add up to the same bits in either order;
+// three or more (rare: a source with three successors of one node) arrive in program order and,
+// inside one instruction, in the order in which the LDS serves the lanes that collide.
+
+__device__ __forceinline__ double spread_link_bwd(const double* __restrict__ rows, const Tile& tl, uint64_t mu,
+                                                  double* __restrict__ acc, const double* __restrict__ sig) {
+  uint64_t rest = tl.mask;
+  uint32_t e = tl.off;
+  double tot = 0.0;
+  while (__ballot(rest != 0) != 0) {  // eight entries per round, all requested first
+    const int c = __popcll(rest);
+    double x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      x[k] = 0.0;
+      if (k < c) x[k] = entry(rows, e + (uint32_t)k);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (rest != 0) {
+        const int s = __builtin_ctzll(rest);
+        rest &= rest - 1;
+        if ((mu >> s) & 1ull) {
+          unsafeAtomicAdd(&acc[s], x[k]);
+          tot = __builtin_fma(sig[s], x[k], tot);
+        }
+      }
+    }
+    e += 8;
+  }
+  return tot;
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const int lane = lane_id();
+  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (u0 >= gv.N) return;
+  const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
+  const NodeIdx* __restrict__ next = cur + gv.Npad;
+  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
+  double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  __shared__ double s_acc[kWavesPerBlock][8][kWave], s_sig[kWavesPerBlock][8][kWave];  // [node of the tile][source]
+  double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
+  double(*sig)[kWave] = s_sig[threadIdx.x / kWave];
+  const NodeIdx me = load_idx(cur + u0 + lane);
+  const uint64_t nodes_active = __ballot(me.mask != 0);
+  if (nodes_active == 0) return;
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (me.mask != 0) {
+    lr.p0 = out_ptr[u0 + lane];
+    lr.p1 = out_ptr[u0 + lane + 1];
+  }
+  int q, q_next, q_nn;
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
+  int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
+#pragma unroll 1
+  for (int c = 0; c < 8; ++c) {
+    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+    nb_next = -1;
+    q_nn = -1;
+    if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+      double sg[8];  // lane = source: sigma and 1/sigma of the nodes' sources, all rows requested first
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint64_t mu_i = readlane64(me.mask, 8 * c + i);
+        const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+        sg[i] = 1.0;
+        if (lane_in(mu_i)) sg[i] = entry(dat, of + rank_in(mu_i));
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        sig[i][lane] = sg[i];
+        acc[i][lane] = 0.0;
+      }
+      __builtin_amdgcn_wave_barrier();
+      const int node = 8 * c + (lane >> 3);
+      const uint64_t mu = shfl64(me.mask, node);
+      const double tot = spread_link_bwd(cf, tile, mu, acc[lane >> 3], sig[lane >> 3]);
+      if (q >= 0 && (tile.mask & mu) != 0) pt[q] += tot;
+      // nodes with more than eight out-links: further tiles into the same accumulators
+      const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
+      for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
+        int qe;
+        const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
+        const double te = spread_link_bwd(cf, extra, mu, acc[lane >> 3], sig[lane >> 3]);
+        if (qe >= 0 && (extra.mask & mu) != 0) pt[qe] += te;
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {  // lane = source: the node's coef row
+        const uint64_t mu_i = readlane64(me.mask, 8 * c + i);
+        const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
+        if (lane_in(mu_i)) entry(cf, of + rank_in(mu_i)) = recip(sg[i]) + acc[i][lane];
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    tile = tile_next;
+    q = q_next;
+    q_next = q_nn;
+  }
+}
+
+template <bool kSlots>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
   int g, nblk;
@@ -1085,7 +1179,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
       const uint64_t mu = shfl64(me.mask, node);
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
       const double tot =
-          kSlots ? slot_bwd<kUnion>(dat, cf, tile, mu, ofu, false, lane) : few_bwd(dat, cf, tile, mu, ofu, false, lane);
+          kSlots ? slot_bwd(dat, cf, tile, mu, ofu, false, lane) : few_bwd(dat, cf, tile, mu, ofu, false, lane);
       if (q >= 0 && (tile.mask & mu) != 0) pt[q] += tot;
       // nodes with more than eight out-links: add the rest to the stored coef
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
@@ -1093,7 +1187,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
         int qe;
         const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
         const double te =
-            kSlots ? slot_bwd<kUnion>(dat, cf, extra, mu, ofu, true, lane) : few_bwd(dat, cf, extra, mu, ofu, true, lane);
+            kSlots ? slot_bwd(dat, cf, extra, mu, ofu, true, lane) : few_bwd(dat, cf, extra, mu, ofu, true, lane);
         if (qe >= 0 && (extra.mask & mu) != 0) pt[qe] += te;
       }
     }

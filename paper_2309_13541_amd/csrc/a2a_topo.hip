@@ -11,7 +11,6 @@
 //   sum    load += per-batch loads, in ascending batch order
 #include <hip/hip_runtime.h>
 
-#include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -53,7 +52,7 @@ namespace {
 enum {
   PROF_INIT = A2A_K_INIT, PROF_BFS = A2A_K_BFS, PROF_OFFSETS = A2A_K_OFFSETS, PROF_FWD = A2A_K_FWD_ROWS,
   PROF_FWD_FEW = A2A_K_FWD_FEW, PROF_FWD_SPREAD = A2A_K_FWD_SPREAD, PROF_BWD = A2A_K_BWD_ROWS,
-  PROF_BWD_FEW = A2A_K_BWD_FEW, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
+  PROF_BWD_FEW = A2A_K_BWD_FEW, PROF_BWD_SPREAD = A2A_K_BWD_SPREAD, PROF_REDUCE = A2A_K_REDUCE, PROF_EXTRACT = A2A_K_EXTRACT,
   PROF_CLASSES = A2A_K_COUNT
 };
 
@@ -211,11 +210,9 @@ int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
 // Which kernel flavour a level gets, from the average number of sources per node on it:
 // below kFewLanes the lanes of a wave stand for (node, link) or (node, source) pairs of eight
 // nodes (k_fwd_few / k_bwd_few), from kSlotLanes on in the (node, source) layout; above, one wave
-// per node with a lane per source (k_fwd_level / k_bwd_level).  Two mixed cases: a forward level
-// above kFewLanes whose predecessor is below it reads whole rows, a lane per (node, link)
-// (k_fwd_spread); a backward level above kFewLanes whose nodes have fewer than kFewLanes sources
-// with a successor starts from the 1/sigma that the forward launch left in coef and is visited
-// by k_bwd_few for those sources only.
+// per node with a lane per source (k_fwd_level / k_bwd_level), unless the level the pass reads
+// from (the one before, forward; the one after, backward) is below kFewLanes: then a lane per
+// (node, link) reads whole rows (k_fwd_spread / k_bwd_spread).
 constexpr double kFewLanes = 8.0;
 constexpr double kSlotLanes = 2.0;
 // Largest topology: a batch's value array (N * 64 entries of 8 bytes) is addressed with 32-bit
@@ -234,17 +231,9 @@ struct Run {
     return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kFewLanes;
   }
   bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
-  // Backward level that starts from coef = 1/sigma (left there by the forward launch of that level)
-  // and only visits the sources with a successor; the deepest level needs no visit at all.
-  bool coef_from_forward(int level, int depth) const {
-    return level == depth || (level > 0 && !few(level) && with_successors(level) < kFewLanes);
-  }
-  // Expected number of sources of a node on level l that have a successor on level l+1.
-  double with_successors(int l) const {
-    if (l < 0 || l + 1 >= (int)lanes_per_node.size()) return 0.0;
-    const double deg = (double)t->E / (double)t->N;
-    return lanes_per_node[l] * (1.0 - std::exp(-deg * lanes_per_node[l + 1] / 64.0));
-  }
+  // Many sources per node on this level, few on the other one the pass looks at.
+  bool fwd_spread(int level) const { return level > 0 && !few(level) && few(level - 1); }
+  bool bwd_spread(int level, int depth) const { return level < depth && !few(level) && few(level + 1); }
   int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
   GroupView view(int batch0, int G) const {
@@ -331,12 +320,11 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   }
   const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
-    const bool few = r.few(l);
-    const bool spread = !few && r.few(l - 1);  // many sources per node here, few on the level before
+    const bool few = r.few(l), spread = r.fwd_spread(l);
     ProfScope ps(t, few ? PROF_FWD_FEW : (spread ? PROF_FWD_SPREAD : PROF_FWD), r.st, l);
     const bool count = t->prof_mode == 2;
-    // levels that the backward pass only adds to get coef = 1/sigma from the forward pass
-    const bool init_coef = gv.coef != nullptr && r.coef_from_forward(l, depth);
+    // the deepest level's coef is 1/sigma: the forward launch leaves it there
+    const bool init_coef = gv.coef != nullptr && l == depth;
     auto launch = [&](auto kernel) {
       kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
     };
@@ -580,18 +568,18 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (t->E > 0) {
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
-      for (int l = depth - 1; l >= 0; --l) {
-        const bool adds = r.coef_from_forward(l, depth);
-        ProfScope ps(t, adds || r.few(l) ? PROF_BWD_FEW : PROF_BWD, st, l);
+      for (int l = depth - 1; l >= 0; --l) {  // the deepest level has no successors: nothing to add
+        const bool spread = r.bwd_spread(l, depth);
+        ProfScope ps(t, r.few(l) ? PROF_BWD_FEW : (spread ? PROF_BWD_SPREAD : PROF_BWD), st, l);
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
-        if (adds)
-          launch(k_bwd_few<true, true>);
+        if (spread)
+          launch(k_bwd_spread);
         else if (!r.few(l))
           launch(k_bwd_level);
         else if (r.slots(l))
-          launch(k_bwd_few<true, false>);
+          launch(k_bwd_few<true>);
         else
-          launch(k_bwd_few<false, false>);
+          launch(k_bwd_few<false>);
       }
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(

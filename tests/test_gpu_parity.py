@@ -304,7 +304,7 @@ def _flavours(a2a, rp, col):
     seen = set()
     for l in range(min(p["depth"] + 1, 63)):  # the profile keeps 64 levels, the last one a catch-all
         lanes = p["pairs_level"][l] / (nb * topo.N)
-        ran = {k: p[k]["ms_level"][l] > 0 for k in ("fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few")}
+        ran = {k: p[k]["ms_level"][l] > 0 for k in ("fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few", "bwd_spread")}
         layout = "_node_source" if lanes >= 2.0 else "_node_link"
         if ran["fwd_rows"]:
             seen.add("fwd_rows")
@@ -315,7 +315,9 @@ def _flavours(a2a, rp, col):
         if ran["bwd_rows"]:
             seen.add("bwd_rows")
         if ran["bwd_few"]:
-            seen.add("bwd_add_only" if ran["fwd_rows"] or ran["fwd_spread"] else "bwd_few" + layout)
+            seen.add("bwd_few" + layout)
+        if ran["bwd_spread"]:
+            seen.add("bwd_spread")
     return seen
 
 
@@ -332,5 +334,5 @@ def test_parity_set_reaches_every_kernel_flavour(a2a):
         print(name, sorted(got), flush=True)
         seen |= got
     want = {"fwd_rows", "fwd_few_node_link", "fwd_few_node_source", "fwd_spread", "bwd_rows", "bwd_few_node_link",
-            "bwd_few_node_source", "bwd_add_only"}
+            "bwd_few_node_source", "bwd_spread"}
     assert want <= seen, want - seen
