@@ -73,6 +73,11 @@ __device__ __forceinline__ const double& entry(const double* __restrict__ dat, u
   return *reinterpret_cast<const double*>(reinterpret_cast<const char*>(dat) + (size_t)(e * 8u));
 }
 
+// Entries 2q and 2q + 1 of a batch's value array in one 16-byte request (q counted in pairs).
+__device__ __forceinline__ double2 entry_pair(const double* __restrict__ dat, uint32_t q) {
+  return *reinterpret_cast<const double2*>(reinterpret_cast<const char*>(dat) + (size_t)(q * 16u));
+}
+
 // 1/x for x >= 1: hardware estimate plus two Newton steps (relative error about 1e-16).
 __device__ __forceinline__ double recip(double x) {
   double r = __builtin_amdgcn_rcp(x);
@@ -931,27 +936,34 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
 // node's sources collect their sums, a lane per source, and write the node's row.
 
 // Adds the entries of this lane's link to acc[source] (the accumulators of this lane's node).
+// The row is read in aligned pairs of entries (16 bytes per request: the requests, one per lane
+// and instruction, are what bounds this kernel); a pair at either end of the row may hold a
+// neighbouring row's entry, which is skipped (the arrays have room for the last pair).
 __device__ __forceinline__ void spread_link(const double* __restrict__ rows, const Tile& tl, uint64_t mu,
                                             double* __restrict__ acc) {
   uint64_t rest = tl.mask;  // sources of the link's row, ascending = its entries in order
-  uint32_t e = tl.off;
-  while (__ballot(rest != 0) != 0) {  // eight entries per round, all requested first
-    const int c = __popcll(rest);
-    double x[8];
+  bool skip = tl.off & 1u;  // the row starts in the upper half of its first pair
+  uint32_t q = tl.off >> 1;
+  while (__ballot(rest != 0) != 0) {  // four pairs per round, all requested first
+    const int n = __popcll(rest) + (skip ? 1 : 0);
+    double2 y[4];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      x[k] = 0.0;
-      if (k < c) x[k] = entry(rows, e + (uint32_t)k);
+    for (int k = 0; k < 4; ++k) {
+      y[k] = make_double2(0.0, 0.0);
+      if (2 * k < n) y[k] = entry_pair(rows, q + (uint32_t)k);
     }
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
+      const double x = (k & 1) ? y[k >> 1].y : y[k >> 1].x;
+      if (k == 0 && skip) continue;
       if (rest != 0) {
         const int s = __builtin_ctzll(rest);
         rest &= rest - 1;
-        if ((mu >> s) & 1ull) unsafeAtomicAdd(&acc[s], x[k]);
+        if ((mu >> s) & 1ull) unsafeAtomicAdd(&acc[s], x);
       }
     }
-    e += 8;
+    skip = false;
+    q += 4;
   }
 }
 
@@ -1041,6 +1053,7 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
 
 __device__ __forceinline__ double spread_link_bwd(const double* __restrict__ rows, const Tile& tl, uint64_t mu,
                                                   double* __restrict__ acc, const double* __restrict__ sig) {
+  // entry by entry: with one or two entries per row, pairs (as in spread_link) only fetch more
   uint64_t rest = tl.mask;
   uint32_t e = tl.off;
   double tot = 0.0;

@@ -111,8 +111,9 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_seen = take(SB * L.Npad * kSub * 8);
     const size_t o_bm = take(SB * L.Lcap * L.Npad * kSub * 8);
     const size_t o_idxb = L.values ? take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx)) : 0;
-    const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8) : 0;
-    const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8) : 0;
+    // + 256: rows are read in aligned 16-byte pairs, the last of which may reach one entry past the end
+    const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
+    const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     if (out) {
       out->off_level_new = o_level_new;
