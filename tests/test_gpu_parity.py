@@ -21,6 +21,28 @@ def a2a():
     return lib
 
 
+def layered_collisions():
+    """64 sources -> 40 nodes (A) -> 8 nodes (B) -> 1..8 leaves each, plus filler nodes with a link into
+    the sources.  Level 1 holds A with all 64 sources per node, level 2 is sparse on average but every
+    node of A has 8 successors there for every source: the backward pass of level 1 adds 8 different
+    coef values per (node, source), which is where the order of additions could show."""
+    S, A, B = 64, 40, 8
+    a0, b0 = S, S + A
+    c0 = b0 + B
+    leaves = sum(range(1, B + 1))
+    N = c0 + leaves + 52
+    rows = [[a0 + (s + 3 * i) % A for i in range(A)] for s in range(S)]
+    rows += [[b0 + (a + i) % B for i in range(B)] for a in range(A)]
+    nxt = c0
+    for b in range(B):
+        rows.append(list(range(nxt, nxt + b + 1)))
+        nxt += b + 1
+    rows += [[] for _ in range(leaves)]
+    rows += [[i % S] for i in range(52)]
+    assert len(rows) == N
+    return gen.csr_from_rows(rows)
+
+
 SMALL = dict(tiny_graphs())
 SMALL.update({
     "torus3x3x3": gen.torus([3, 3, 3]),
@@ -42,6 +64,7 @@ SMALL.update({
     "chain_2pow54": gen.csr_from_rows([[i + 1, i + 1] for i in range(54)] + [[]]),
     # path counts from node 0 are tiny, from node 1 they reach 2^30
     "late_blowup": gen.csr_from_rows([[]] + [[i + 1, i + 1] for i in range(1, 31)] + [[]]),
+    "layered_collisions": layered_collisions(),
 })
 
 
@@ -171,6 +194,14 @@ def test_workspace_size_and_reruns(a2a, oracle):
         a = run_link_loads(topo, max_ws=ws)
         b = run_link_loads(topo, max_ws=ws)
         assert np.array_equal(a[0], b[0])
+    # the same where eight different values are added per (node, source) in one LDS instruction
+    rp2, col2 = SMALL["layered_collisions"]
+    topo2 = a2a.Topology(rp2, col2)
+    first = run_link_loads(topo2, 0, 64)  # the 64 designed sources alone: one batch, levels as described
+    assert_loads_close(first[0], oracle.run(rp2, col2, 0, 64).load)
+    for _ in range(5):
+        assert np.array_equal(run_link_loads(topo2, 0, 64)[0], first[0])
+    topo2.close()
     d_full = run_distances(topo)
     d_one = run_distances(topo, max_ws=topo.workspace_bytes(topo.N, a2a.WS_SIGMA | a2a.WS_MINIMAL))
     for x, y in zip(d_full[:3], d_one[:3]):
