@@ -142,16 +142,8 @@ __device__ __forceinline__ double group_sum8(const double (&x)[8], int lane) {
   return keep + xor_lanes<4>(send);  // lane l: sum of x[l & 7] over the eight lanes of its group
 }
 
-// The same over the whole wave: every lane l gets the sum over all 64 lanes of x[l & 7].
-__device__ __forceinline__ double wave_sum8(const double (&x)[8], int lane) {
-  double w = group_sum8(x, lane);
-  w += xor_lanes<8>(w);
-  w += xor_lanes<16>(w);
-  w += xor_lanes<32>(w);
-  return w;
-}
-
-// The same sums through LDS: each lane stores its eight values (one row of 64 per value, rows
+// Eight 64-lane sums at once through LDS: on return every lane l holds the sum over all 64 lanes
+// of x[l & 7].  Each lane stores its eight values (one row of 64 per value, rows
 // padded by one to spread the banks), lane l then adds the eight values of x[l & 7] that lanes
 // 8*(l>>3) .. 8*(l>>3)+7 stored, and three exchange steps add the eight partial sums.  Seven
 // plus three additions on the vector ALU instead of 4+2+1+3 select-and-add rounds; the moves
