@@ -278,7 +278,14 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     if (sn != valid) {
       uint64_t acc = 0;
       const int p1 = in_ptr[v + 1];
-      for (int p = in_ptr[v]; p < p1; ++p) acc |= prev[(size_t)in_col[p] * kSub];
+      for (int p = in_ptr[v]; p < p1; p += 8) {  // eight in-links at a time, all requests in flight
+        int u[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) u[j] = p + j < p1 ? in_col[p + j] : -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (u[j] >= 0) acc |= prev[(size_t)u[j] * kSub];
+      }
       nw = acc & ~sn;
       if (nw) gv.seen[si] = sn | nw;
     }
