@@ -274,20 +274,33 @@ int run_bfs(const Run& r, const GroupView& gv, int* depth) {
     ProfScope ps(t, PROF_INIT, r.st);
     k_init_group<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv);
   }
+  // Levels are launched kLevelChunk at a time and the "frontier not empty" flags read back once per
+  // chunk: the depth is data dependent, and a host round trip per level costs more than the few
+  // empty levels a chunk may run past the last one.
+  constexpr int kLevelChunk = 8;
   int d = 0;
   int l = 1;
-  for (; l < L.Lcap; ++l) {
-    {
+  bool done = false;
+  while (!done && l < L.Lcap) {
+    const int first = l, last = std::min(l + kLevelChunk, L.Lcap);  // levels first .. last-1
+    for (; l < last; ++l) {
       ProfScope ps(t, PROF_BFS, r.st, l);
       k_bfs_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l,
                                                                    r.level_new());
     }
-    HIP_TRY(hipMemcpyAsync(t->h_pinned, r.level_new() + l, 4, hipMemcpyDeviceToHost, r.st));
+    HIP_TRY(hipMemcpyAsync(t->h_pinned, r.level_new() + first, (size_t)(last - first) * 4, hipMemcpyDeviceToHost,
+                           r.st));
     HIP_TRY(hipStreamSynchronize(r.st));
-    if (*(volatile int*)t->h_pinned == 0) break;
-    d = l;
+    const int32_t* flags = (const int32_t*)t->h_pinned;
+    for (int k = first; k < last; ++k) {
+      if (flags[k - first] == 0) {
+        done = true;
+        break;
+      }
+      d = k;
+    }
   }
-  if (l == L.Lcap) return A2A_ERR_LEVEL_OVERFLOW;
+  if (!done) return A2A_ERR_LEVEL_OVERFLOW;
   HIP_TRY(hipGetLastError());
   // how full each level is decides which kernel flavour the passes use
   try {
