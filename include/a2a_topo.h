@@ -18,9 +18,10 @@
  *     buffer and the stream; the library owns only the opaque handle (a device copy of the
  *     out- and in-neighbour CSR, a few KB of pinned host memory).
  *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
- *     default stream).  a2a_distances and a2a_link_loads wait on that stream once per BFS
- *     level (the number of levels is data dependent) and return with the remaining work
- *     enqueued; a2a_schedule_bound waits for its result.
+ *     default stream).  a2a_distances and a2a_link_loads wait on that stream once per eight
+ *     BFS levels and once more per batch group (the number of levels and how full they are
+ *     is data dependent and decides what is launched next) and return with the remaining
+ *     work enqueued; a2a_schedule_bound waits for its result.
  *   - Every function returns an a2a_status (0 = A2A_OK, negative = error); nothing throws,
  *     aborts or prints.  On error the outputs are unspecified.
  *   - Sources are processed in batches of 64 (one bit of a 64-bit mask per source); several
