@@ -90,7 +90,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (sources would shard across GPUs with one "
-              "ordered sum of E doubles at the end; see DESIGN.md). Use --gpus 1.", file=sys.stderr)
+              "ordered sum of E doubles at the end). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
