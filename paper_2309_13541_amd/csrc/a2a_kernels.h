@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 namespace a2a_dev {
 
@@ -71,6 +72,14 @@ __device__ __forceinline__ double& entry(double* __restrict__ dat, uint32_t e) {
 }
 __device__ __forceinline__ const double& entry(const double* __restrict__ dat, uint32_t e) {
   return *reinterpret_cast<const double*>(reinterpret_cast<const char*>(dat) + (size_t)(e * 8u));
+}
+
+// The same position in the batch's single-precision copy of sigma.
+__device__ __forceinline__ float& entry(float* __restrict__ datf, uint32_t e) {
+  return *reinterpret_cast<float*>(reinterpret_cast<char*>(datf) + (size_t)(e * 4u));
+}
+__device__ __forceinline__ const float& entry(const float* __restrict__ datf, uint32_t e) {
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(datf) + (size_t)(e * 4u));
 }
 
 // Entries 2q and 2q + 1 of a batch's value array in one 16-byte request (q counted in pairs).
@@ -215,6 +224,8 @@ struct GroupView {
   uint64_t* seen;     // [SB][Npad][kSub]
   NodeIdx* idxb;      // [G][Lcap][Npad]  mask + row offset per batch (nullptr: distances only)
   double* dat;        // [G][Npad*64]  level-compact sigma (nullptr: distances only)
+  float* datf;        // [G][Npad*64]  the same in single precision, for the levels that are gathered
+                      //               from row by row while every path count is below 2^24
   double* coef;       // [G][Npad*64]  level-compact coef (link loads only)
   int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level;
                       //                       after k_scan_blocks: first entry of the block's rows
@@ -421,14 +432,15 @@ __device__ __forceinline__ Tile tile_request_idx(const NodeIdx* __restrict__ lev
 
 // Issues the (up to) eight row gathers of node i of the current tile: lanes in mk & want read
 // their entry of the link's row.  Returns the number of (source, link) pairs.
-__device__ __forceinline__ int gather8(const double* __restrict__ rows, const Tile& tile, int i, uint64_t want,
-                                       double (&x)[8], uint64_t (&m)[8]) {
+template <typename T>
+__device__ __forceinline__ int gather8(const T* __restrict__ rows, const Tile& tile, int i, uint64_t want,
+                                       T (&x)[8], uint64_t (&m)[8]) {
   int pairs = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const uint64_t mk = readlane64(tile.mask, 8 * i + j);
     m[j] = mk & want;
-    x[j] = 0.0;
+    x[j] = (T)0;
     if (m[j] != 0) {  // uniform: skip links that carry nothing for this node
       const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)tile.off, 8 * i + j);
       pairs += __popcll(m[j]);
@@ -440,11 +452,14 @@ __device__ __forceinline__ int gather8(const double* __restrict__ rows, const Ti
 
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
 // cf (may be null): the deepest level's coef is just 1/sigma, which goes there now.
-__device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __restrict__ cf, const NodeIdx& me,
-                                           int node, const double (&x)[8]) {
+// datf (may be null): single-precision copy for the next level's gathers.  The gathered values
+// are converted here, where they are used, so that the requests stay in flight until then.
+template <typename T>
+__device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __restrict__ cf, float* __restrict__ datf,
+                                           const NodeIdx& me, int node, const T (&x)[8]) {
   double a = 0.0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) a += x[j];
+  for (int j = 0; j < 8; ++j) a += (double)x[j];
   const uint64_t newv = readlane64(me.mask, node);
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
   bool big = false;
@@ -452,15 +467,17 @@ __device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __r
     const uint32_t e = of + rank_in(newv);
     entry(dat, e) = a;
     if (cf != nullptr) entry(cf, e) = recip(a);
+    if (datf != nullptr) entry(datf, e) = (float)a;
     big = a >= kTwo53;
   }
   return big;
 }
 
-template <bool kCountDag>
+// kF32: gather from the single-precision copy (the host has made sure it is exact).
+template <bool kCountDag, bool kF32>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
-            int level, bool init_coef, long long* __restrict__ misc) {
+            int level, bool init_coef, bool store_f32, long long* __restrict__ misc) {
   int g, nblk;
   if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
@@ -470,6 +487,13 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
+  float* __restrict__ datf = store_f32 ? gv.datf + (size_t)g * gv.Npad * 64 : nullptr;
+  using Row = typename std::conditional<kF32, float, double>::type;
+  const Row* __restrict__ rows;
+  if constexpr (kF32)
+    rows = gv.datf + (size_t)g * gv.Npad * 64;
+  else
+    rows = dat;
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -489,15 +513,15 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
     nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
-      double xa[8], xb[8];
+      Row xa[8], xb[8];
       uint64_t m[8];
-      int pairs = gather8(dat, tile, 0, readlane64(me.mask, 8 * c), xa, m);
+      int pairs = gather8(rows, tile, 0, readlane64(me.mask, 8 * c), xa, m);
 #pragma unroll 1
       for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
-        pairs += gather8(dat, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
-        inexact |= fwd_finish(dat, cf, me, 8 * c + i, xa);
-        if (i + 2 < 8) pairs += gather8(dat, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
-        inexact |= fwd_finish(dat, cf, me, 8 * c + i + 1, xb);
+        pairs += gather8(rows, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
+        inexact |= fwd_finish(dat, cf, datf, me, 8 * c + i, xa);
+        if (i + 2 < 8) pairs += gather8(rows, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
+        inexact |= fwd_finish(dat, cf, datf, me, 8 * c + i + 1, xb);
       }
       if (kCountDag) dag += pairs;
       // nodes with more than eight in-links: add the rest to the stored entries
@@ -507,18 +531,19 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
 #pragma unroll 1
         for (int i = 0; i < 8; ++i) {
           const uint64_t newv = readlane64(me.mask, 8 * c + i);
-          const int np = gather8(dat, extra, i, newv, xa, m);
+          const int np = gather8(rows, extra, i, newv, xa, m);
           if (np == 0) continue;
           if (kCountDag) dag += np;
           double a = 0.0;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) a += xa[j];
+          for (int j = 0; j < 8; ++j) a += (double)xa[j];
           const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
           if (lane_in(newv)) {
             const uint32_t pos = of + rank_in(newv);
             a += entry(dat, pos);
             entry(dat, pos) = a;
             if (cf != nullptr) entry(cf, pos) = recip(a);
+            if (datf != nullptr) entry(datf, pos) = (float)a;
             inexact |= a >= kTwo53;
           }
         }
@@ -969,7 +994,7 @@ __device__ __forceinline__ void spread_link(const double* __restrict__ rows, con
 template <bool kCountDag>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
-             bool init_coef, long long* __restrict__ misc) {
+             bool init_coef, bool store_f32, long long* __restrict__ misc) {
   int g, nblk;
   if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
@@ -979,6 +1004,7 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
+  float* __restrict__ datf = store_f32 ? gv.datf + (size_t)g * gv.Npad * 64 : nullptr;
   __shared__ double s_acc[kWavesPerBlock][8][kWave];  // [node of the tile][source]
   double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + v0 + lane);
@@ -1024,6 +1050,7 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
           const uint32_t e = of + rank_in(newv);
           entry(dat, e) = a;
           if (cf != nullptr) entry(cf, e) = recip(a);
+          if (datf != nullptr) entry(datf, e) = (float)a;
           inexact |= a >= kTwo53;
         }
       }

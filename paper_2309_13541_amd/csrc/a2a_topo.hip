@@ -26,6 +26,7 @@ struct a2a_topo {
   int32_t N = 0;
   int64_t E = 0;
   int32_t dmax = 0;
+  int32_t dmax_in = 0;  // largest in-degree
   int32_t level_bound = 0;
   int32_t* d_out_ptr = nullptr;
   int32_t* d_out_col = nullptr;
@@ -45,6 +46,7 @@ struct a2a_topo {
   mutable int64_t prof_calls = 0;
   mutable int32_t prof_depth = 0;
   mutable int32_t prof_groups = 0;
+  mutable uint64_t prof_narrow = 0;
 };
 
 namespace {
@@ -77,6 +79,7 @@ struct Layout {
   size_t off_bm = 0;         // uint64 [SB][Lcap][Npad][kSub]
   size_t off_idxb = 0;       // NodeIdx [G][Lcap][Npad]        (with sigma / loads)
   size_t off_dat = 0;        // double [G][Npad*64]  sigma
+  size_t off_datf = 0;       // float [G][Npad*64]   sigma in single precision
   size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
   size_t off_part = 0;       // double [G][Epad]
   size_t total = 0;
@@ -113,6 +116,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_idxb = L.values ? take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx)) : 0;
     // + 256: rows are read in aligned 16-byte pairs, the last of which may reach one entry past the end
     const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
+    const size_t o_datf = L.values ? take((size_t)G * L.Npad * 64 * 4) : 0;
     const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     if (out) {
@@ -126,6 +130,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->SB = (int)SB;
       out->off_idxb = o_idxb;
       out->off_dat = o_dat;
+      out->off_datf = o_datf;
       out->off_coef = o_coef;
       out->off_part = o_part;
       out->total = off;
@@ -234,6 +239,10 @@ struct Run {
   bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
   // Many sources per node on this level, few on the other one the pass looks at.
   bool fwd_spread(int level) const { return level > 0 && !few(level) && few(level - 1); }
+  bool fwd_rows(int level) const { return level > 0 && !few(level) && !few(level - 1); }
+  // Path counts on `level` are at most (largest in-degree)^level: below 2^24 they are exact in
+  // single precision, and a row-by-row forward launch of the next level gathers half the bytes.
+  bool narrow(int level) const { return (double)level * std::log2((double)std::max(t->dmax_in, 2)) < 24.0; }
   bool bwd_spread(int level, int depth) const { return level < depth && !few(level) && few(level + 1); }
   int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
@@ -243,6 +252,7 @@ struct Run {
     gv.idxb = L.values ? (NodeIdx*)(ws + L.off_idxb) : nullptr;
     gv.seen = (uint64_t*)(ws + L.off_seen);
     gv.dat = L.values ? (double*)(ws + L.off_dat) : nullptr;
+    gv.datf = L.values ? (float*)(ws + L.off_datf) : nullptr;
     gv.coef = L.loads ? (double*)(ws + L.off_coef) : nullptr;
     gv.bsum = (int*)(ws + L.off_bsum);
     gv.ltot = (long long*)(ws + L.off_ltot);
@@ -339,17 +349,26 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     const bool count = t->prof_mode == 2;
     // the deepest level's coef is 1/sigma: the forward launch leaves it there
     const bool init_coef = gv.coef != nullptr && l == depth;
+    // a single-precision copy of this level for the next one, if that one gathers row by row
+    const bool store_f32 = l < depth && r.fwd_rows(l + 1) && r.narrow(l);
+    const bool use_f32 = r.fwd_rows(l) && r.narrow(l - 1);
     auto launch = [&](auto kernel) {
+      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, store_f32, r.misc());
+    };
+    auto launch_few = [&](auto kernel) {
       kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
     };
     if (spread)
       count ? launch(k_fwd_spread<true>) : launch(k_fwd_spread<false>);
-    else if (!few)
-      count ? launch(k_fwd_level<true>) : launch(k_fwd_level<false>);
+    else if (!few && use_f32) {
+      if (t->prof_mode != 0 && l < 64) t->prof_narrow |= 1ull << l;
+      count ? launch(k_fwd_level<true, true>) : launch(k_fwd_level<false, true>);
+    } else if (!few)
+      count ? launch(k_fwd_level<true, false>) : launch(k_fwd_level<false, false>);
     else if (r.slots(l))
-      count ? launch(k_fwd_few<true, true>) : launch(k_fwd_few<false, true>);
+      count ? launch_few(k_fwd_few<true, true>) : launch_few(k_fwd_few<false, true>);
     else
-      count ? launch(k_fwd_few<true, false>) : launch(k_fwd_few<false, false>);
+      count ? launch_few(k_fwd_few<true, false>) : launch_few(k_fwd_few<false, false>);
   }
   HIP_TRY(hipGetLastError());
   if (t->prof_mode == 2) {  // shortest-path links into each level, for the roofline accounting
@@ -427,6 +446,7 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
     std::vector<int32_t> fill(in_ptr.begin(), in_ptr.end() - 1);
     for (int32_t u = 0; u < N; ++u)  // ascending link id => in-lists are stable in link order
       for (int32_t p = row_ptr[u]; p < row_ptr[u + 1]; ++p) in_col[(size_t)fill[col_idx[p]]++] = u;
+    for (int32_t v = 0; v < N; ++v) t->dmax_in = std::max(t->dmax_in, in_ptr[(size_t)v + 1] - in_ptr[v]);
     const int e_out = host_ecc0(N, row_ptr, col_idx);
     const int e_in = host_ecc0(N, in_ptr.data(), in_col.data());
     t->level_bound = (e_out >= 0 && e_in >= 0) ? e_out + e_in : N - 1;
@@ -706,6 +726,7 @@ int a2a_profile_enable(a2a_topo* t, int mode) {
   t->prof_calls = 0;
   t->prof_depth = 0;
   t->prof_groups = 0;
+  t->prof_narrow = 0;
   t->prof_mode = mode;
   std::memset(t->prof_pairs_level, 0, sizeof(t->prof_pairs_level));
   std::memset(t->prof_dag_level, 0, sizeof(t->prof_dag_level));
@@ -735,6 +756,7 @@ int a2a_profile_read(a2a_topo* t, a2a_profile* out) {
   out->calls = t->prof_calls;
   out->depth = t->prof_depth;
   out->groups = t->prof_groups;
+  out->narrow_levels = t->prof_narrow;
   return A2A_OK;
 }
 

@@ -43,6 +43,22 @@ def layered_collisions():
     return gen.csr_from_rows(rows)
 
 
+def dense_layers(K=7, W=64, seed=77):
+    """K layers of W nodes in a cycle, every node linked to about 9 in 10 nodes of the next layer.  Every level
+    from 1 to K is well filled (64/K sources per node) and the largest in-degree is 63: the forward launches of
+    levels 2..5 may read the level before in single precision (path counts on level 4 are below 63^4 < 2^24),
+    those of levels 6..K must not (the counts there go past 2^24, up to about 58^6)."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for k in range(K):
+        nxt = ((k + 1) % K) * W
+        for _ in range(W):
+            keep = rng.random(W) < 0.9
+            keep[rng.integers(W)] = True
+            rows.append([nxt + int(j) for j in np.nonzero(keep)[0]])
+    return gen.csr_from_rows(rows)
+
+
 SMALL = dict(tiny_graphs())
 SMALL.update({
     "torus3x3x3": gen.torus([3, 3, 3]),
@@ -65,6 +81,7 @@ SMALL.update({
     # path counts from node 0 are tiny, from node 1 they reach 2^30
     "late_blowup": gen.csr_from_rows([[]] + [[i + 1, i + 1] for i in range(1, 31)] + [[]]),
     "layered_collisions": layered_collisions(),
+    "dense_layers": dense_layers(),
 })
 
 
@@ -338,7 +355,7 @@ def _flavours(a2a, rp, col):
         ran = {k: p[k]["ms_level"][l] > 0 for k in ("fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few", "bwd_spread")}
         layout = "_node_source" if lanes >= 2.0 else "_node_link"
         if ran["fwd_rows"]:
-            seen.add("fwd_rows")
+            seen.add("fwd_rows_f32" if (p["narrow_levels"] >> l) & 1 else "fwd_rows_f64")
         if ran["fwd_few"]:
             seen.add("fwd_few" + layout)
         if ran["fwd_spread"]:
@@ -364,6 +381,6 @@ def test_parity_set_reaches_every_kernel_flavour(a2a):
         got = _flavours(a2a, rp, col)
         print(name, sorted(got), flush=True)
         seen |= got
-    want = {"fwd_rows", "fwd_few_node_link", "fwd_few_node_source", "fwd_spread", "bwd_rows", "bwd_few_node_link",
+    want = {"fwd_rows_f32", "fwd_rows_f64", "fwd_few_node_link", "fwd_few_node_source", "fwd_spread", "bwd_rows", "bwd_few_node_link",
             "bwd_few_node_source", "bwd_spread"}
     assert want <= seen, want - seen
