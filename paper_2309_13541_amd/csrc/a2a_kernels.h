@@ -82,9 +82,22 @@ __device__ __forceinline__ const float& entry(const float* __restrict__ datf, ui
   return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(datf) + (size_t)(e * 4u));
 }
 
-// Entries 2q and 2q + 1 of a batch's value array in one 16-byte request (q counted in pairs).
-__device__ __forceinline__ double2 entry_pair(const double* __restrict__ dat, uint32_t q) {
-  return *reinterpret_cast<const double2*>(reinterpret_cast<const char*>(dat) + (size_t)(q * 16u));
+// 16-byte piece number q of a batch's value array in one request: two doubles or four floats.
+// The words stay as they are until piece_get picks an entry, so that nothing waits for the data
+// before it is needed.
+template <typename T>
+__device__ __forceinline__ uint4 piece(const T* __restrict__ rows, uint32_t q) {
+  return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(rows) + (size_t)(q * 16u));
+}
+template <typename T>
+__device__ __forceinline__ double piece_get(const uint4& r, int k);
+template <>
+__device__ __forceinline__ double piece_get<double>(const uint4& r, int k) {
+  return k ? __hiloint2double((int)r.w, (int)r.z) : __hiloint2double((int)r.y, (int)r.x);
+}
+template <>
+__device__ __forceinline__ double piece_get<float>(const uint4& r, int k) {
+  return (double)__uint_as_float(k == 0 ? r.x : k == 1 ? r.y : k == 2 ? r.z : r.w);
 }
 
 // 1/x for x >= 1: hardware estimate plus two Newton steps (relative error about 1e-16).
@@ -223,9 +236,13 @@ struct GroupView {
   uint64_t* bm;       // [SB][Lcap][Npad][kSub] BFS level masks L_l[v]
   uint64_t* seen;     // [SB][Npad][kSub]
   NodeIdx* idxb;      // [G][Lcap][Npad]  mask + row offset per batch (nullptr: distances only)
-  double* dat;        // [G][Npad*64]  level-compact sigma (nullptr: distances only)
-  float* datf;        // [G][Npad*64]  the same in single precision, for the levels that are gathered
-                      //               from row by row while every path count is below 2^24
+  double* dat;        // [G][Npad*64]  level-compact sigma of the levels from f32_levels on (nullptr:
+                      //               distances only)
+  float* datf;        // the same memory: sigma of the levels below f32_levels, entry e = the e-th float
+                      //               of the batch's array.  Levels on which every path count is certain
+                      //               to be below 2^24 keep it in single precision only (exact, half the
+                      //               bytes); they come first in the array, so their floats end before
+                      //               the first double of a later level begins
   double* coef;       // [G][Npad*64]  level-compact coef (link loads only)
   int* bsum;          // [SB*kSub][Lcap][nb64] newly reached pairs per 64-node block and level;
                       //                       after k_scan_blocks: first entry of the block's rows
@@ -235,7 +252,20 @@ struct GroupView {
   size_t Epad;
   int N, Npad, Lcap, G, SB, bpb, nb64, inflight;
   int src_begin, src_count, batch0;
+  int f32_levels;     // >= 1
 };
+
+// The batch's sigma array of the given precision.
+template <typename T>
+__device__ __forceinline__ T* sigma_rows(const GroupView& gv, int g);
+template <>
+__device__ __forceinline__ double* sigma_rows<double>(const GroupView& gv, int g) {
+  return gv.dat + (size_t)g * gv.Npad * 64;
+}
+template <>
+__device__ __forceinline__ float* sigma_rows<float>(const GroupView& gv, int g) {
+  return gv.datf + (size_t)g * gv.Npad * 128;  // the batch's array counted in floats
+}
 
 __device__ __forceinline__ size_t bm_at(const GroupView& gv, int sb, int level, int v, int k) {
   return ((((size_t)sb * gv.Lcap + level) * gv.Npad) + v) * kSub + k;
@@ -261,7 +291,7 @@ __global__ void __launch_bounds__(kBfsBlock) k_init_group(GroupView gv) {
   const uint64_t bit = is_src ? (1ull << j) : 0ull;
   gv.bm[bm_at(gv, sb, 0, v, k)] = bit;
   gv.seen[((size_t)sb * gv.Npad + v) * kSub + k] = bit;
-  if (gv.dat != nullptr && is_src) gv.dat[(size_t)g * gv.Npad * 64 + j] = 1.0;
+  if (gv.datf != nullptr && is_src) gv.datf[(size_t)g * gv.Npad * 128 + j] = 1.0f;  // level 0 is always narrow
   if (v == 0) {
     gv.ltot[(size_t)g * gv.Lcap] = cnt;
     if (g < gv.G)
@@ -452,11 +482,11 @@ __device__ __forceinline__ int gather8(const T* __restrict__ rows, const Tile& t
 
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
 // cf (may be null): the deepest level's coef is just 1/sigma, which goes there now.
-// datf (may be null): single-precision copy for the next level's gathers.  The gathered values
-// are converted here, where they are used, so that the requests stay in flight until then.
-template <typename T>
-__device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __restrict__ cf, float* __restrict__ datf,
-                                           const NodeIdx& me, int node, const T (&x)[8]) {
+// The gathered values are widened here, where they are used, so that the requests stay in
+// flight until then.
+template <typename TIn, typename TOut>
+__device__ __forceinline__ bool fwd_finish(TOut* __restrict__ out, double* __restrict__ cf, const NodeIdx& me, int node,
+                                           const TIn (&x)[8]) {
   double a = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) a += (double)x[j];
@@ -465,19 +495,18 @@ __device__ __forceinline__ bool fwd_finish(double* __restrict__ dat, double* __r
   bool big = false;
   if (lane_in(newv)) {
     const uint32_t e = of + rank_in(newv);
-    entry(dat, e) = a;
+    entry(out, e) = (TOut)a;
     if (cf != nullptr) entry(cf, e) = recip(a);
-    if (datf != nullptr) entry(datf, e) = (float)a;
     big = a >= kTwo53;
   }
   return big;
 }
 
-// kF32: gather from the single-precision copy (the host has made sure it is exact).
-template <bool kCountDag, bool kF32>
+// TIn / TOut: precision in which the level before / this level keeps sigma (the host's choice).
+template <bool kCountDag, typename TIn, typename TOut>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
-            int level, bool init_coef, bool store_f32, long long* __restrict__ misc) {
+            int level, bool init_coef, long long* __restrict__ misc) {
   int g, nblk;
   if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
@@ -485,15 +514,9 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   if (v0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
-  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
+  TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  float* __restrict__ datf = store_f32 ? gv.datf + (size_t)g * gv.Npad * 64 : nullptr;
-  using Row = typename std::conditional<kF32, float, double>::type;
-  const Row* __restrict__ rows;
-  if constexpr (kF32)
-    rows = gv.datf + (size_t)g * gv.Npad * 64;
-  else
-    rows = dat;
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -513,15 +536,15 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
     const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
     nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
-      Row xa[8], xb[8];
+      TIn xa[8], xb[8];
       uint64_t m[8];
       int pairs = gather8(rows, tile, 0, readlane64(me.mask, 8 * c), xa, m);
 #pragma unroll 1
       for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
         pairs += gather8(rows, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
-        inexact |= fwd_finish(dat, cf, datf, me, 8 * c + i, xa);
+        inexact |= fwd_finish(out, cf, me, 8 * c + i, xa);
         if (i + 2 < 8) pairs += gather8(rows, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
-        inexact |= fwd_finish(dat, cf, datf, me, 8 * c + i + 1, xb);
+        inexact |= fwd_finish(out, cf, me, 8 * c + i + 1, xb);
       }
       if (kCountDag) dag += pairs;
       // nodes with more than eight in-links: add the rest to the stored entries
@@ -540,10 +563,9 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
           const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
           if (lane_in(newv)) {
             const uint32_t pos = of + rank_in(newv);
-            a += entry(dat, pos);
-            entry(dat, pos) = a;
+            a += (double)entry(out, pos);
+            entry(out, pos) = (TOut)a;
             if (cf != nullptr) entry(cf, pos) = recip(a);
-            if (datf != nullptr) entry(datf, pos) = (float)a;
             inexact |= a >= kTwo53;
           }
         }
@@ -590,19 +612,22 @@ __device__ __forceinline__ double link_sums(double (&x)[8], const uint64_t (&m)[
 }
 
 // Own sigma of a node (1 in lanes that are not on this level), requested together with the rows.
-__device__ __forceinline__ double own_sigma(const double* __restrict__ dat, const NodeIdx& me, int node) {
+template <typename TS>
+__device__ __forceinline__ TS own_sigma(const TS* __restrict__ dat, const NodeIdx& me, int node) {
   const uint64_t mu = readlane64(me.mask, node);
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
-  double s = 1.0;
+  TS s = (TS)1;
   if (lane_in(mu)) s = entry(dat, of + rank_in(mu));
   return s;
 }
 
 // coef of a node from its sigma and the gathered coef rows (x, overwritten by the products that
 // the link loads are made of); `add`: further round of a node with more than eight links.
-__device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const NodeIdx& me, int node, int i, double s,
+template <typename TS>
+__device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const NodeIdx& me, int node, int i, TS sigma,
                                              double (&x)[8], const uint64_t (&m)[8], int pairs, bool add, int lane,
                                              double tot_l, double* sum8_buf) {
+  const double s = (double)sigma;
   double a = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -619,6 +644,8 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
   return tot_l;
 }
 
+// TS: precision in which this level keeps sigma.
+template <typename TS>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
             int level) {
@@ -629,7 +656,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
-  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   __shared__ double s_sum8[kWavesPerBlock][kSum8Doubles];
@@ -656,7 +683,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
       double xa[8], xb[8];
       uint64_t ma[8], mb[8];
       double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i
-      double sa = own_sigma(dat, me, 8 * c), sb;
+      TS sa = own_sigma(dat, me, 8 * c), sb;
       int pa = gather8(cf, tile, 0, readlane64(me.mask, 8 * c), xa, ma), pb;
 #pragma unroll 1
       for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
@@ -670,7 +697,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
         tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, xb, mb, pb, false, lane, tot_l, sum8_buf);
       }
       const uint64_t mu_lane = shfl64(me.mask, 8 * c + (lane >> 3));
-      if (q >= 0 && (tile.mask & mu_lane) != 0) pt[q] += tot_l;
+      if (q >= 0 && (tile.mask & mu_lane) != 0) unsafeAtomicAdd(&pt[q], tot_l);
       // nodes with more than eight out-links: add the rest to the stored coef
       const int p0 = __shfl(lr.p0, 8 * c + (lane >> 3), kWave), p1 = __shfl(lr.p1, 8 * c + (lane >> 3), kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
@@ -684,7 +711,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
           sa = own_sigma(dat, me, 8 * c + i);
           tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, true, lane, tot_l, sum8_buf);
         }
-        if (qe >= 0 && (extra.mask & mu_lane) != 0) pt[qe] += tot_l;
+        if (qe >= 0 && (extra.mask & mu_lane) != 0) unsafeAtomicAdd(&pt[qe], tot_l);
       }
     }
     tile = tile_next;
@@ -723,11 +750,12 @@ __device__ __forceinline__ double bcast8(double x) {
 // The next (up to) eight sources of `rest`, lowest first: x[k] = the entry of the k-th of them in
 // the link's row (mk, ofk), 0 if the link does not carry it or there is no k-th source.  All
 // requests are issued before any value is used.
-__device__ __forceinline__ void few_fetch8(const double* __restrict__ rows, uint64_t mk, uint32_t ofk, uint64_t& rest,
-                                           double (&x)[8]) {
+template <typename T>
+__device__ __forceinline__ void few_fetch8(const T* __restrict__ rows, uint64_t mk, uint32_t ofk, uint64_t& rest,
+                                           T (&x)[8]) {
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    x[k] = 0.0;
+    x[k] = (T)0;
     if (rest != 0) {
       const int s = __builtin_ctzll(rest);
       rest &= rest - 1;
@@ -738,19 +766,23 @@ __device__ __forceinline__ void few_fetch8(const double* __restrict__ rows, uint
 
 // sigma of the node's sources from one tile of in-links (mu, ofu: the node's own mask and row).
 // Lane j of the node ends up with the sum for the node's j-th source and writes that entry.
-__device__ __forceinline__ bool few_fwd(double* __restrict__ dat, double* __restrict__ cf, const Tile& tl, uint64_t mu,
-                                        uint32_t ofu, bool add, int lane) {
+template <typename TIn, typename TOut>
+__device__ __forceinline__ bool few_fwd(const TIn* __restrict__ rows, TOut* __restrict__ out, double* __restrict__ cf,
+                                        const Tile& tl, uint64_t mu, uint32_t ofu, bool add, int lane) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   int left = __popcll(mu) - (lane & 7);  // > 0: this lane owns a source of the current eight
   bool big = false;
   while (__ballot(rest != 0) != 0) {
+    TIn xr[8];
+    few_fetch8(rows, tl.mask, tl.off, rest, xr);
     double x[8];
-    few_fetch8(dat, tl.mask, tl.off, rest, x);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x[k] = (double)xr[k];
     double a = group_sum8(x, lane);
     if (left > 0 && !(add && a == 0.0)) {
-      if (add) a += entry(dat, e);
-      entry(dat, e) = a;
+      if (add) a += (double)entry(out, e);
+      entry(out, e) = (TOut)a;
       if (cf != nullptr) entry(cf, e) = recip(a);
       big |= a >= kTwo53;
     }
@@ -761,7 +793,8 @@ __device__ __forceinline__ bool few_fwd(double* __restrict__ dat, double* __rest
 }
 
 // coef of the node's sources and this lane's link load from one tile of out-links.
-__device__ __forceinline__ double few_bwd(const double* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
+template <typename TS>
+__device__ __forceinline__ double few_bwd(const TS* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
                                           uint64_t mu, uint32_t ofu, bool add, int lane) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
@@ -770,8 +803,9 @@ __device__ __forceinline__ double few_bwd(const double* __restrict__ dat, double
   while (__ballot(rest != 0) != 0) {
     double x[8];
     few_fetch8(cf, tl.mask, tl.off, rest, x);
-    double sg = 1.0;  // lane j: sigma of the node's j-th source of these eight
-    if (left > 0) sg = entry(dat, e);
+    TS sg_own = (TS)1;  // lane j: sigma of the node's j-th source of these eight
+    if (left > 0) sg_own = entry(dat, e);
+    const double sg = (double)sg_own;
     acc = __builtin_fma(bcast8<0>(sg), x[0], acc);
     acc = __builtin_fma(bcast8<1>(sg), x[1], acc);
     acc = __builtin_fma(bcast8<2>(sg), x[2], acc);
@@ -823,15 +857,16 @@ __device__ __forceinline__ int slot_take8(uint64_t& rest, int k) {
 }
 
 // x[j] = entry of source s in the row of link j of this lane's node (0 if not carried).
-template <int kJ>
-__device__ __forceinline__ double slot_fetch(const double* __restrict__ rows, const Tile& tl, int s) {
+template <int kJ, typename T>
+__device__ __forceinline__ T slot_fetch(const T* __restrict__ rows, const Tile& tl, int s) {
   const uint64_t mk = bcast8<kJ>(tl.mask);
   const uint32_t ofk = bcast8<kJ>(tl.off);
-  double x = 0.0;
+  T x = (T)0;
   if (s >= 0 && ((mk >> s) & 1ull)) x = entry(rows, ofk + below(mk, s));
   return x;
 }
-__device__ __forceinline__ void slot_fetch8(const double* __restrict__ rows, const Tile& tl, int s, double (&x)[8]) {
+template <typename T>
+__device__ __forceinline__ void slot_fetch8(const T* __restrict__ rows, const Tile& tl, int s, T (&x)[8]) {
   x[0] = slot_fetch<0>(rows, tl, s);
   x[1] = slot_fetch<1>(rows, tl, s);
   x[2] = slot_fetch<2>(rows, tl, s);
@@ -842,21 +877,22 @@ __device__ __forceinline__ void slot_fetch8(const double* __restrict__ rows, con
   x[7] = slot_fetch<7>(rows, tl, s);
 }
 
-__device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, double* __restrict__ cf, const Tile& tl, uint64_t mu,
-                                         uint32_t ofu, bool add, int lane) {
+template <typename TIn, typename TOut>
+__device__ __forceinline__ bool slot_fwd(const TIn* __restrict__ rows, TOut* __restrict__ out, double* __restrict__ cf,
+                                         const Tile& tl, uint64_t mu, uint32_t ofu, bool add, int lane) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   bool big = false;
   while (__ballot(rest != 0) != 0) {
     const int s = slot_take8(rest, lane & 7);
-    double x[8];
-    slot_fetch8(dat, tl, s, x);
+    TIn x[8];
+    slot_fetch8(rows, tl, s, x);
     double a = 0.0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a += x[j];
+    for (int j = 0; j < 8; ++j) a += (double)x[j];
     if (s >= 0 && !(add && a == 0.0)) {
-      if (add) a += entry(dat, e);
-      entry(dat, e) = a;
+      if (add) a += (double)entry(out, e);
+      entry(out, e) = (TOut)a;
       if (cf != nullptr) entry(cf, e) = recip(a);
       big |= a >= kTwo53;
     }
@@ -866,7 +902,8 @@ __device__ __forceinline__ bool slot_fwd(double* __restrict__ dat, double* __res
 }
 
 // Returns, in lane 8i+j, the load of link j of node i from this tile.
-__device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
+template <typename TS>
+__device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
                                            uint64_t mu, uint32_t ofu, bool add, int lane) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
@@ -877,8 +914,9 @@ __device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, doubl
     const int s = slot_take8(rest, lane & 7);
     double x[8];
     slot_fetch8(cf, tl, s, x);
-    double sg = 1.0;
-    if (s >= 0) sg = entry(dat, e);
+    TS sg_own = (TS)1;
+    if (s >= 0) sg_own = entry(dat, e);
+    const double sg = (double)sg_own;
     double a = 0.0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -894,7 +932,7 @@ __device__ __forceinline__ double slot_bwd(const double* __restrict__ dat, doubl
   return group_sum8(p, lane);
 }
 
-template <bool kCountDag, bool kSlots>
+template <bool kCountDag, bool kSlots, typename TIn, typename TOut>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
           bool init_coef, long long* __restrict__ misc) {
@@ -905,7 +943,8 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
   if (v0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
-  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
+  TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
@@ -929,13 +968,13 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
-      inexact |= kSlots ? slot_fwd(dat, cf, tile, mu, ofu, false, lane) : few_fwd(dat, cf, tile, mu, ofu, false, lane);
+      inexact |= kSlots ? slot_fwd(rows, out, cf, tile, mu, ofu, false, lane) : few_fwd(rows, out, cf, tile, mu, ofu, false, lane);
       if (kCountDag) dag += __popcll(tile.mask & mu);
       // nodes with more than eight in-links: add the rest to the stored entries
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
-        inexact |= kSlots ? slot_fwd(dat, cf, extra, mu, ofu, true, lane) : few_fwd(dat, cf, extra, mu, ofu, true, lane);
+        inexact |= kSlots ? slot_fwd(rows, out, cf, extra, mu, ofu, true, lane) : few_fwd(rows, out, cf, extra, mu, ofu, true, lane);
         if (kCountDag) dag += __popcll(extra.mask & mu);
       }
     }
@@ -960,41 +999,42 @@ k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col
 // node's sources collect their sums, a lane per source, and write the node's row.
 
 // Adds the entries of this lane's link to acc[source] (the accumulators of this lane's node).
-// The row is read in aligned pairs of entries (16 bytes per request: the requests, one per lane
-// and instruction, are what bounds this kernel); a pair at either end of the row may hold a
-// neighbouring row's entry, which is skipped (the arrays have room for the last pair).
-__device__ __forceinline__ void spread_link(const double* __restrict__ rows, const Tile& tl, uint64_t mu,
+// The row is read in aligned 16-byte pieces (two or four entries per request: the requests, one
+// per lane and instruction, are what bounds this kernel); a piece at either end of the row may
+// hold a neighbouring row's entries, which are skipped (the arrays have room for the last piece).
+template <typename T>
+__device__ __forceinline__ void spread_link(const T* __restrict__ rows, const Tile& tl, uint64_t mu,
                                             double* __restrict__ acc) {
+  constexpr int kPer = 16 / (int)sizeof(T);
   uint64_t rest = tl.mask;  // sources of the link's row, ascending = its entries in order
-  bool skip = tl.off & 1u;  // the row starts in the upper half of its first pair
-  uint32_t q = tl.off >> 1;
-  while (__ballot(rest != 0) != 0) {  // four pairs per round, all requested first
-    const int n = __popcll(rest) + (skip ? 1 : 0);
-    double2 y[4];
+  int skip = (int)(tl.off & (uint32_t)(kPer - 1));  // entries of the first piece that come before the row
+  uint32_t q = tl.off / (uint32_t)kPer;
+  while (__ballot(rest != 0) != 0) {  // four pieces per round, all requested first
+    const int n = __popcll(rest) + skip;
+    uint4 y[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      y[k] = make_double2(0.0, 0.0);
-      if (2 * k < n) y[k] = entry_pair(rows, q + (uint32_t)k);
+      y[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (kPer * k < n) y[k] = piece(rows, q + (uint32_t)k);
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const double x = (k & 1) ? y[k >> 1].y : y[k >> 1].x;
-      if (k == 0 && skip) continue;
+    for (int k = 0; k < 4 * kPer; ++k) {
+      if (k < kPer - 1 && k < skip) continue;
       if (rest != 0) {
         const int s = __builtin_ctzll(rest);
         rest &= rest - 1;
-        if ((mu >> s) & 1ull) unsafeAtomicAdd(&acc[s], x);
+        if ((mu >> s) & 1ull) unsafeAtomicAdd(&acc[s], piece_get<T>(y[k / kPer], k % kPer));
       }
     }
-    skip = false;
+    skip = 0;
     q += 4;
   }
 }
 
-template <bool kCountDag>
+template <bool kCountDag, typename TIn, typename TOut>
 __global__ void __launch_bounds__(kBlock)
 k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
-             bool init_coef, bool store_f32, long long* __restrict__ misc) {
+             bool init_coef, long long* __restrict__ misc) {
   int g, nblk;
   if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
   const int lane = lane_id();
@@ -1002,9 +1042,9 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
   if (v0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
-  double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
+  TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  float* __restrict__ datf = store_f32 ? gv.datf + (size_t)g * gv.Npad * 64 : nullptr;
   __shared__ double s_acc[kWavesPerBlock][8][kWave];  // [node of the tile][source]
   double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + v0 + lane);
@@ -1031,13 +1071,13 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
       __builtin_amdgcn_wave_barrier();
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
-      spread_link(dat, tile, mu, acc[lane >> 3]);
+      spread_link(rows, tile, mu, acc[lane >> 3]);
       if (kCountDag) dag += __popcll(tile.mask & mu);
       // nodes with more than eight in-links: further tiles into the same accumulators
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
-        spread_link(dat, extra, mu, acc[lane >> 3]);
+        spread_link(rows, extra, mu, acc[lane >> 3]);
         if (kCountDag) dag += __popcll(extra.mask & mu);
       }
       __builtin_amdgcn_wave_barrier();
@@ -1048,9 +1088,8 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
         if (lane_in(newv)) {
           const double a = acc[i][lane];
           const uint32_t e = of + rank_in(newv);
-          entry(dat, e) = a;
+          entry(out, e) = (TOut)a;
           if (cf != nullptr) entry(cf, e) = recip(a);
-          if (datf != nullptr) entry(datf, e) = (float)a;
           inexact |= a >= kTwo53;
         }
       }
@@ -1107,6 +1146,7 @@ __device__ __forceinline__ double spread_link_bwd(const double* __restrict__ row
   return tot;
 }
 
+template <typename TS>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
   int g, nblk;
@@ -1116,7 +1156,7 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
   if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
-  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   __shared__ double s_acc[kWavesPerBlock][8][kWave], s_sig[kWavesPerBlock][8][kWave];  // [node of the tile][source]
@@ -1141,16 +1181,18 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
     q_nn = -1;
     if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
-      double sg[8];  // lane = source: sigma and 1/sigma of the nodes' sources, all rows requested first
+      TS sg_own[8];  // lane = source: sigma of the nodes' sources, all rows requested first
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const uint64_t mu_i = readlane64(me.mask, 8 * c + i);
         const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-        sg[i] = 1.0;
-        if (lane_in(mu_i)) sg[i] = entry(dat, of + rank_in(mu_i));
+        sg_own[i] = (TS)1;
+        if (lane_in(mu_i)) sg_own[i] = entry(dat, of + rank_in(mu_i));
       }
+      double sg[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
+        sg[i] = (double)sg_own[i];
         sig[i][lane] = sg[i];
         acc[i][lane] = 0.0;
       }
@@ -1158,14 +1200,14 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
       const double tot = spread_link_bwd(cf, tile, mu, acc[lane >> 3], sig[lane >> 3]);
-      if (q >= 0 && (tile.mask & mu) != 0) pt[q] += tot;
+      if (q >= 0 && (tile.mask & mu) != 0) unsafeAtomicAdd(&pt[q], tot);
       // nodes with more than eight out-links: further tiles into the same accumulators
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         int qe;
         const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
         const double te = spread_link_bwd(cf, extra, mu, acc[lane >> 3], sig[lane >> 3]);
-        if (qe >= 0 && (extra.mask & mu) != 0) pt[qe] += te;
+        if (qe >= 0 && (extra.mask & mu) != 0) unsafeAtomicAdd(&pt[qe], te);
       }
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -1182,7 +1224,7 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
   }
 }
 
-template <bool kSlots>
+template <bool kSlots, typename TS>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
   int g, nblk;
@@ -1192,7 +1234,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
   if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
-  const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const NodeIdx me = load_idx(cur + u0 + lane);
@@ -1219,7 +1261,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
       const double tot =
           kSlots ? slot_bwd(dat, cf, tile, mu, ofu, false, lane) : few_bwd(dat, cf, tile, mu, ofu, false, lane);
-      if (q >= 0 && (tile.mask & mu) != 0) pt[q] += tot;
+      if (q >= 0 && (tile.mask & mu) != 0) unsafeAtomicAdd(&pt[q], tot);
       // nodes with more than eight out-links: add the rest to the stored coef
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
@@ -1227,7 +1269,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
         const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
         const double te =
             kSlots ? slot_bwd(dat, cf, extra, mu, ofu, true, lane) : few_bwd(dat, cf, extra, mu, ofu, true, lane);
-        if (qe >= 0 && (extra.mask & mu) != 0) pt[qe] += te;
+        if (qe >= 0 && (extra.mask & mu) != 0) unsafeAtomicAdd(&pt[qe], te);
       }
     }
     tile = tile_next;
@@ -1348,6 +1390,7 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
   const int t = (int)threadIdx.x;
   const int v0 = tile * kWave;
   const double* __restrict__ dat = gv.dat + (size_t)g * gv.Npad * 64;
+  const float* __restrict__ datf = gv.datf + (size_t)g * gv.Npad * 128;
   for (int i = 0; i < kWave; ++i) t_s[t][i] = 0.0;
   for (int l = 0; l <= depth; ++l) {
     const NodeIdx me = load_idx(gv.idxb + ((size_t)g * gv.Lcap + l) * gv.Npad + v0 + t);
@@ -1357,7 +1400,10 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
       todo &= todo - 1;
       const uint64_t mk = readlane64(me.mask, i);
       const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, i);
-      if ((mk >> t) & 1ull) t_s[t][i] = dat[of + rank_in(mk)];
+      if ((mk >> t) & 1ull) {
+        const uint32_t e = of + rank_in(mk);
+        t_s[t][i] = l < gv.f32_levels ? (double)datf[e] : dat[e];
+      }
     }
   }
   __syncthreads();

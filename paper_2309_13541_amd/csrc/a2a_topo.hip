@@ -78,8 +78,9 @@ struct Layout {
   size_t off_seen = 0;       // uint64 [SB][Npad][kSub]
   size_t off_bm = 0;         // uint64 [SB][Lcap][Npad][kSub]
   size_t off_idxb = 0;       // NodeIdx [G][Lcap][Npad]        (with sigma / loads)
-  size_t off_dat = 0;        // double [G][Npad*64]  sigma
-  size_t off_datf = 0;       // float [G][Npad*64]   sigma in single precision
+  size_t off_dat = 0;        // [G][Npad*64] x 8 bytes: sigma.  Entry e of a level kept in double precision is
+                             // the e-th double, that of a level kept in single precision the e-th float of
+                             // the same array: the single-precision levels come first, so the two never meet
   size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
   size_t off_part = 0;       // double [G][Epad]
   size_t total = 0;
@@ -116,7 +117,6 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_idxb = L.values ? take((size_t)G * L.Lcap * L.Npad * sizeof(NodeIdx)) : 0;
     // + 256: rows are read in aligned 16-byte pairs, the last of which may reach one entry past the end
     const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
-    const size_t o_datf = L.values ? take((size_t)G * L.Npad * 64 * 4) : 0;
     const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     if (out) {
@@ -130,7 +130,6 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->SB = (int)SB;
       out->off_idxb = o_idxb;
       out->off_dat = o_dat;
-      out->off_datf = o_datf;
       out->off_coef = o_coef;
       out->off_part = o_part;
       out->total = off;
@@ -239,10 +238,16 @@ struct Run {
   bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
   // Many sources per node on this level, few on the other one the pass looks at.
   bool fwd_spread(int level) const { return level > 0 && !few(level) && few(level - 1); }
-  bool fwd_rows(int level) const { return level > 0 && !few(level) && !few(level - 1); }
-  // Path counts on `level` are at most (largest in-degree)^level: below 2^24 they are exact in
-  // single precision, and a row-by-row forward launch of the next level gathers half the bytes.
+  // Path counts on `level` are at most (largest in-degree)^level: while that is below 2^24 the level
+  // keeps sigma in single precision (exact: whole numbers a float holds), which halves what the
+  // forward pass writes and gathers and what the backward pass reads of it.  If a level is narrow,
+  // so are all before it.
   bool narrow(int level) const { return (double)level * std::log2((double)std::max(t->dmax_in, 2)) < 24.0; }
+  int f32_levels() const {
+    int n = 1;
+    while (n < L.Lcap && narrow(n)) ++n;
+    return n;
+  }
   bool bwd_spread(int level, int depth) const { return level < depth && !few(level) && few(level + 1); }
   int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
@@ -252,7 +257,7 @@ struct Run {
     gv.idxb = L.values ? (NodeIdx*)(ws + L.off_idxb) : nullptr;
     gv.seen = (uint64_t*)(ws + L.off_seen);
     gv.dat = L.values ? (double*)(ws + L.off_dat) : nullptr;
-    gv.datf = L.values ? (float*)(ws + L.off_datf) : nullptr;
+    gv.datf = L.values ? (float*)(ws + L.off_dat) : nullptr;
     gv.coef = L.loads ? (double*)(ws + L.off_coef) : nullptr;
     gv.bsum = (int*)(ws + L.off_bsum);
     gv.ltot = (long long*)(ws + L.off_ltot);
@@ -270,6 +275,7 @@ struct Run {
     gv.src_begin = src_begin;
     gv.src_count = src_count;
     gv.batch0 = batch0;
+    gv.f32_levels = f32_levels();
     return gv;
   }
 };
@@ -349,26 +355,30 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     const bool count = t->prof_mode == 2;
     // the deepest level's coef is 1/sigma: the forward launch leaves it there
     const bool init_coef = gv.coef != nullptr && l == depth;
-    // a single-precision copy of this level for the next one, if that one gathers row by row
-    const bool store_f32 = l < depth && r.fwd_rows(l + 1) && r.narrow(l);
-    const bool use_f32 = r.fwd_rows(l) && r.narrow(l - 1);
     auto launch = [&](auto kernel) {
-      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, store_f32, r.misc());
-    };
-    auto launch_few = [&](auto kernel) {
       kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
     };
-    if (spread)
-      count ? launch(k_fwd_spread<true>) : launch(k_fwd_spread<false>);
-    else if (!few && use_f32) {
-      if (t->prof_mode != 0 && l < 64) t->prof_narrow |= 1ull << l;
-      count ? launch(k_fwd_level<true, true>) : launch(k_fwd_level<false, true>);
-    } else if (!few)
-      count ? launch(k_fwd_level<true, false>) : launch(k_fwd_level<false, false>);
-    else if (r.slots(l))
-      count ? launch_few(k_fwd_few<true, true>) : launch_few(k_fwd_few<false, true>);
-    else
-      count ? launch_few(k_fwd_few<true, false>) : launch_few(k_fwd_few<false, false>);
+    // precision of the level gathered from (tin) and of the one written (tout)
+    auto pick = [&](auto tin, auto tout) {
+      using TIn = decltype(tin);
+      using TOut = decltype(tout);
+      if (spread)
+        count ? launch(k_fwd_spread<true, TIn, TOut>) : launch(k_fwd_spread<false, TIn, TOut>);
+      else if (!few)
+        count ? launch(k_fwd_level<true, TIn, TOut>) : launch(k_fwd_level<false, TIn, TOut>);
+      else if (r.slots(l))
+        count ? launch(k_fwd_few<true, true, TIn, TOut>) : launch(k_fwd_few<false, true, TIn, TOut>);
+      else
+        count ? launch(k_fwd_few<true, false, TIn, TOut>) : launch(k_fwd_few<false, false, TIn, TOut>);
+    };
+    if (r.narrow(l)) {
+      pick(float{}, float{});
+    } else if (r.narrow(l - 1)) {
+      pick(float{}, double{});
+    } else {
+      pick(double{}, double{});
+    }
+    if (t->prof_mode != 0 && l < 64 && r.narrow(l - 1)) t->prof_narrow |= 1ull << l;
   }
   HIP_TRY(hipGetLastError());
   if (t->prof_mode == 2) {  // shortest-path links into each level, for the roofline accounting
@@ -606,14 +616,21 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
         const bool spread = r.bwd_spread(l, depth);
         ProfScope ps(t, r.few(l) ? PROF_BWD_FEW : (spread ? PROF_BWD_SPREAD : PROF_BWD), st, l);
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
-        if (spread)
-          launch(k_bwd_spread);
-        else if (!r.few(l))
-          launch(k_bwd_level);
-        else if (r.slots(l))
-          launch(k_bwd_few<true>);
+        auto pick = [&](auto ts) {  // precision of this level's sigma
+          using TS = decltype(ts);
+          if (spread)
+            launch(k_bwd_spread<TS>);
+          else if (!r.few(l))
+            launch(k_bwd_level<TS>);
+          else if (r.slots(l))
+            launch(k_bwd_few<true, TS>);
+          else
+            launch(k_bwd_few<false, TS>);
+        };
+        if (r.narrow(l))
+          pick(float{});
         else
-          launch(k_bwd_few<false>);
+          pick(double{});
       }
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(

@@ -59,6 +59,42 @@ def dense_layers(K=7, W=64, seed=77):
     return gen.csr_from_rows(rows)
 
 
+def funnel_layers(widths, seed):
+    """Nodes 0..63 (the sources the tests run it with) -> 4 merge nodes (16 sources each) -> 4 hubs -> layers
+    of the given widths; hub h reaches 70 % of the first layer (a different window each), a node of a later
+    layer has 9..16 in-links from the layer before.  For those 64 sources, level l >= 3 is layer l - 3 (all its
+    nodes from the second layer on, with almost all sources each): the widths choose how full each level is,
+    hence which kernel flavour runs it, and the largest in-degree, 16, fixes from where on path counts are kept
+    in double precision (level 6: 16^6 = 2^24).  The four groups of sources see different counts."""
+    rng = np.random.default_rng(seed)
+    first = 64 + 4 + 4
+    starts = [first]
+    for w in widths:
+        starts.append(starts[-1] + w)
+    rows = [[64 + s // 16] for s in range(64)]
+    rows += [[68 + h] for h in range(4)]
+    w0 = widths[0]
+    span = max(1, (7 * w0) // 10)
+    rows += [[first + (h * (w0 - span) // 3 + i) % w0 for i in range(span)] for h in range(4)]
+    rows += [[] for _ in range(starts[-1] - first)]
+    for k in range(1, len(widths)):
+        wp = widths[k - 1]
+        for j in range(widths[k]):
+            deg = min(wp, int(rng.integers(9, 17)))
+            for u in rng.choice(wp, size=deg, replace=False):
+                rows[starts[k - 1] + int(u)].append(starts[k] + j)
+    return gen.csr_from_rows([sorted(r) for r in rows])
+
+
+# level:            3    4    5    6    7    8    9   10
+FUNNELS = {
+    "funnel_a": ([100, 100, 30, 100, 100, 4, 100, 30], 5),   # level 6: dense after sparse
+    "funnel_b": ([100, 100, 100, 100, 30, 100, 4, 100], 6),  # level 6: dense after dense
+    "funnel_c": ([100, 100, 100, 30, 100, 100, 30, 100], 7),  # level 6: a few sources per node
+    "funnel_d": ([100, 100, 100, 4, 100, 100, 100, 30], 8),   # level 6: under two sources per node
+}
+
+
 SMALL = dict(tiny_graphs())
 SMALL.update({
     "torus3x3x3": gen.torus([3, 3, 3]),
@@ -104,6 +140,25 @@ def test_small_graphs_everything(a2a, oracle, name):
     assert dtot == int(o.dist_sum.sum()) and lflags == o.flags
     if len(col):
         assert_loads_close(load, o.load)
+    topo.close()
+
+
+@pytest.mark.parametrize("name", sorted(FUNNELS))
+def test_funnels_precision_boundary(a2a, oracle, name):
+    """Graphs whose levels 3..10 (for sources 0..63) are as full as chosen, with the change from single- to
+    double-precision path counts at level 6: every kernel flavour on either side of it and across it."""
+    rp, col = funnel_layers(*FUNNELS[name])
+    print(f"case {name} N={len(rp) - 1} E={len(col)}", flush=True)
+    o = oracle.run(rp, col, 0, 64, want_dist=True, want_sigma=True)
+    assert not (o.flags & 1)
+    topo = a2a.Topology(rp, col)
+    dist, sigma, dsum, unr, flags = run_distances(topo, 0, 64)
+    assert np.array_equal(dist, o.dist) and np.array_equal(dsum, o.dist_sum)
+    assert unr == o.unreachable and flags == o.flags
+    assert_sigma_equal(sigma, o.sigma)
+    load, dtot, lflags = run_link_loads(topo, 0, 64)
+    assert dtot == int(o.dist_sum.sum()) and lflags == o.flags
+    assert_loads_close(load, o.load)
     topo.close()
 
 
@@ -338,41 +393,45 @@ def test_disabled_links_and_hosts(a2a, oracle):
             topo.close()
 
 
-def _flavours(a2a, rp, col):
-    """Which kernel flavour each level got, read off the per-level launch times."""
+def _flavours(a2a, rp, col, src_count=None):
+    """Which kernel flavour each level got, read off the per-level launch times, with the precision of the
+    path counts it read and wrote (f = single, d = double)."""
     import torch
     topo = a2a.Topology(rp, col)
-    ws = topo.alloc_workspace(topo.N, a2a.WS_LOADS)
+    cnt = topo.N if src_count is None else src_count
+    ws = topo.alloc_workspace(cnt, a2a.WS_LOADS)
     load = torch.empty(max(topo.E, 1), dtype=torch.float64, device="cuda")
     topo.profile_enable(1)
-    topo.link_loads(0, topo.N, load=load, workspace=ws)
+    topo.link_loads(0, cnt, load=load, workspace=ws)
     p = topo.profile_read()
     topo.profile_enable(0)
-    nb = (topo.N + 63) // 64
+    nb = (cnt + 63) // 64
     seen = set()
-    for l in range(min(p["depth"] + 1, 63)):  # the profile keeps 64 levels, the last one a catch-all
+    top = min(p["depth"], 62)  # the profile keeps 64 levels, the last one a catch-all
+    narrow = [True] + [bool((p["narrow_levels"] >> (l + 1)) & 1) for l in range(top + 1)]  # narrow[l]: level l in single
+    for l in range(top + 1):
         lanes = p["pairs_level"][l] / (nb * topo.N)
         ran = {k: p[k]["ms_level"][l] > 0 for k in ("fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few", "bwd_spread")}
         layout = "_node_source" if lanes >= 2.0 else "_node_link"
-        if ran["fwd_rows"]:
-            seen.add("fwd_rows_f32" if (p["narrow_levels"] >> l) & 1 else "fwd_rows_f64")
-        if ran["fwd_few"]:
-            seen.add("fwd_few" + layout)
-        if ran["fwd_spread"]:
-            seen.add("fwd_spread")
-        if ran["bwd_rows"]:
-            seen.add("bwd_rows")
-        if ran["bwd_few"]:
-            seen.add("bwd_few" + layout)
-        if ran["bwd_spread"]:
-            seen.add("bwd_spread")
+        fwd = "_" + ("f" if l >= 1 and narrow[l - 1] else "d") + ("f" if narrow[l] else "d")
+        bwd = "_f" if narrow[l] else "_d"
+        if l == top:  # whether the deepest level seen is narrow is not in the bit mask
+            fwd = bwd = None
+        for k, name in (("fwd_rows", "fwd_rows"), ("fwd_few", "fwd_few" + layout), ("fwd_spread", "fwd_spread")):
+            if ran[k] and fwd:
+                seen.add(name + fwd)
+        for k, name in (("bwd_rows", "bwd_rows"), ("bwd_few", "bwd_few" + layout), ("bwd_spread", "bwd_spread")):
+            if ran[k] and bwd:
+                seen.add(name + bwd)
+    topo.close()
     return seen
 
 
 def test_parity_set_reaches_every_kernel_flavour(a2a):
-    """The level kernels come in flavours picked from how full a level is; the graphs of
-    test_small_graphs_everything must between them run every one (else parity says nothing
-    about the ones left out)."""
+    """The level kernels come in flavours picked from how full a level is and from the precision the path
+    counts of the levels involved are kept in; the graphs of test_small_graphs_everything and
+    test_funnels_precision_boundary must between them run every one (else parity says nothing about the ones
+    left out)."""
     seen = set()
     for name in sorted(SMALL):
         rp, col = SMALL[name]
@@ -381,6 +440,11 @@ def test_parity_set_reaches_every_kernel_flavour(a2a):
         got = _flavours(a2a, rp, col)
         print(name, sorted(got), flush=True)
         seen |= got
-    want = {"fwd_rows_f32", "fwd_rows_f64", "fwd_few_node_link", "fwd_few_node_source", "fwd_spread", "bwd_rows", "bwd_few_node_link",
-            "bwd_few_node_source", "bwd_spread"}
-    assert want <= seen, want - seen
+    for name in sorted(FUNNELS):
+        got = _flavours(a2a, *funnel_layers(*FUNNELS[name]), src_count=64)
+        print(name, sorted(got), flush=True)
+        seen |= got
+    want = {f + p for f in ("fwd_rows", "fwd_few_node_link", "fwd_few_node_source", "fwd_spread")
+            for p in ("_ff", "_fd", "_dd")}
+    want |= {f + p for f in ("bwd_rows", "bwd_few_node_link", "bwd_few_node_source", "bwd_spread") for p in ("_f", "_d")}
+    assert want <= seen, sorted(want - seen)
