@@ -26,6 +26,9 @@
  *     aborts or prints.  On error the outputs are unspecified.
  *   - Sources are processed in batches of 64 (one bit of a 64-bit mask per source); several
  *     batches advance level by level together, as many as the workspace holds.
+ *   - All arithmetic is in double precision.  Inside the workspace the path counts of BFS level
+ *     l are kept as floats while (largest in-degree)^l < 2^24, i.e. while every one of them is
+ *     certain to be a whole number that a float holds exactly; results do not depend on it.
  */
 #ifndef A2A_TOPO_H
 #define A2A_TOPO_H
@@ -222,8 +225,7 @@ typedef enum a2a_prof_kernel {
   A2A_K_INIT = 0,  /* level 0 set-up */
   A2A_K_BFS,       /* one BFS level */
   A2A_K_OFFSETS,   /* row offsets of the level-compact arrays */
-  A2A_K_FWD_ROWS,  /* forward level, one wave per node (well-filled level); reads the level before in
-                      single precision while its path counts are provably below 2^24 */
+  A2A_K_FWD_ROWS,  /* forward level, one wave per node (well-filled level) */
   A2A_K_FWD_FEW,   /* forward level with few sources per node: lanes = (node, link) or (node, source) */
   A2A_K_FWD_SPREAD, /* forward level, many sources per node, short rows on the level before */
   A2A_K_BWD_ROWS,  /* backward level, one wave per node */
@@ -244,8 +246,10 @@ typedef struct a2a_profile {
   int64_t calls;                               /* a2a_distances + a2a_link_loads calls since enable */
   int32_t depth;                               /* deepest BFS level seen */
   int32_t groups;                              /* batch groups processed */
-  uint64_t narrow_levels;                      /* bit l: a forward launch of level l (< 64) gathered the
-                                                  single-precision copy of the level before */
+  uint64_t narrow_levels;                      /* bit l: a forward launch of level l (< 64) read the path
+                                                  counts of level l-1 in single precision (the library
+                                                  keeps them so while (largest in-degree)^level < 2^24:
+                                                  exact, half the bytes) */
 } a2a_profile;
 int a2a_profile_enable(a2a_topo* topo, int mode);
 int a2a_profile_read(a2a_topo* topo, a2a_profile* out);
