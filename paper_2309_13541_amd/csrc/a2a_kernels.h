@@ -82,6 +82,19 @@ __device__ __forceinline__ const float& entry(const float* __restrict__ datf, ui
   return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(datf) + (size_t)(e * 4u));
 }
 
+// Returns x unchanged, as far as the compiler can tell a new value: a conversion applied to the
+// result stays here instead of being moved up to the load that produced x, where it would make
+// the wave wait for that load before the next one is issued.
+__device__ __forceinline__ float hold(float x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+__device__ __forceinline__ double hold(double x) { return x; }  // nothing is converted
+__device__ __forceinline__ uint32_t hold(uint32_t x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 // 16-byte piece number q of a batch's value array in one request: two doubles or four floats.
 // The words stay as they are until piece_get picks an entry, so that nothing waits for the data
 // before it is needed.
@@ -97,7 +110,7 @@ __device__ __forceinline__ double piece_get<double>(const uint4& r, int k) {
 }
 template <>
 __device__ __forceinline__ double piece_get<float>(const uint4& r, int k) {
-  return (double)__uint_as_float(k == 0 ? r.x : k == 1 ? r.y : k == 2 ? r.z : r.w);
+  return (double)__uint_as_float(hold(k == 0 ? r.x : k == 1 ? r.y : k == 2 ? r.z : r.w));
 }
 
 // 1/x for x >= 1: hardware estimate plus two Newton steps (relative error about 1e-16).
@@ -489,7 +502,7 @@ __device__ __forceinline__ bool fwd_finish(TOut* __restrict__ out, double* __res
                                            const TIn (&x)[8]) {
   double a = 0.0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) a += (double)x[j];
+  for (int j = 0; j < 8; ++j) a += (double)hold(x[j]);
   const uint64_t newv = readlane64(me.mask, node);
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
   bool big = false;
@@ -559,7 +572,7 @@ k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
           if (kCountDag) dag += np;
           double a = 0.0;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) a += (double)xa[j];
+          for (int j = 0; j < 8; ++j) a += (double)hold(xa[j]);
           const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
           if (lane_in(newv)) {
             const uint32_t pos = of + rank_in(newv);
@@ -627,7 +640,7 @@ template <typename TS>
 __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const NodeIdx& me, int node, int i, TS sigma,
                                              double (&x)[8], const uint64_t (&m)[8], int pairs, bool add, int lane,
                                              double tot_l, double* sum8_buf) {
-  const double s = (double)sigma;
+  const double s = (double)hold(sigma);
   double a = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -778,7 +791,7 @@ __device__ __forceinline__ bool few_fwd(const TIn* __restrict__ rows, TOut* __re
     few_fetch8(rows, tl.mask, tl.off, rest, xr);
     double x[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) x[k] = (double)xr[k];
+    for (int k = 0; k < 8; ++k) x[k] = (double)hold(xr[k]);
     double a = group_sum8(x, lane);
     if (left > 0 && !(add && a == 0.0)) {
       if (add) a += (double)entry(out, e);
@@ -805,7 +818,7 @@ __device__ __forceinline__ double few_bwd(const TS* __restrict__ dat, double* __
     few_fetch8(cf, tl.mask, tl.off, rest, x);
     TS sg_own = (TS)1;  // lane j: sigma of the node's j-th source of these eight
     if (left > 0) sg_own = entry(dat, e);
-    const double sg = (double)sg_own;
+    const double sg = (double)hold(sg_own);
     acc = __builtin_fma(bcast8<0>(sg), x[0], acc);
     acc = __builtin_fma(bcast8<1>(sg), x[1], acc);
     acc = __builtin_fma(bcast8<2>(sg), x[2], acc);
@@ -889,7 +902,7 @@ __device__ __forceinline__ bool slot_fwd(const TIn* __restrict__ rows, TOut* __r
     slot_fetch8(rows, tl, s, x);
     double a = 0.0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a += (double)x[j];
+    for (int j = 0; j < 8; ++j) a += (double)hold(x[j]);
     if (s >= 0 && !(add && a == 0.0)) {
       if (add) a += (double)entry(out, e);
       entry(out, e) = (TOut)a;
@@ -916,7 +929,7 @@ __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* _
     slot_fetch8(cf, tl, s, x);
     TS sg_own = (TS)1;
     if (s >= 0) sg_own = entry(dat, e);
-    const double sg = (double)sg_own;
+    const double sg = (double)hold(sg_own);
     double a = 0.0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -1192,7 +1205,7 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
       double sg[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        sg[i] = (double)sg_own[i];
+        sg[i] = (double)hold(sg_own[i]);
         sig[i][lane] = sg[i];
         acc[i][lane] = 0.0;
       }
