@@ -9,15 +9,17 @@
 // levels follow each other.  Every reachable (source, node) pair owns exactly one entry, at the
 // same position in two arrays: sigma(s,v) (number of shortest paths, Sec. 5.2), written by the
 // forward pass, and coef(s,v) = (1 + delta(s,v)) / sigma(s,v), written by the backward pass,
-// where delta is the traffic forwarded through v under the equal split of Sec. 5.2.  A link (u,w) is used by the sources
-// in L_l[u] & L_{l+1}[w]; a gather of row (l,u) therefore reads popcount(L_l[u]) values instead
-// of a 64-wide row, and a node's row is written once per pass instead of once per level.
+// where delta is the traffic forwarded through v under the equal split of Sec. 5.2.  A link
+// (u,w) is used by the sources in L_l[u] & L_{l+1}[w]; a gather of row (l,u) therefore reads
+// popcount(L_l[u]) values instead of a 64-wide row, and a node's row is written once per pass
+// instead of once per level.  coef is always double; sigma is kept as floats on the first
+// levels, as long as (largest in-degree)^level < 2^24 bounds every path count of the level by a
+// whole number that a float holds exactly, and as doubles from then on (GroupView::f32_levels).
 #pragma once
 
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <type_traits>
 
 namespace a2a_dev {
 
