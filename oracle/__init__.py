@@ -10,6 +10,7 @@ exact-rational oracle for tiny graphs (enumerates every shortest path).
 from .binding import (  # noqa: F401
     build,
     run,
+    run_demand,
     bound,
     bound_cap,
     tree_sum,

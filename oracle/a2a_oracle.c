@@ -24,9 +24,9 @@
  * when it is visited).  Threads only split the source range; each owns a private
  * load vector and the vectors are merged in thread order.
  *
- * Pins (tests/test_oracle_*.py, tests/test_capacities.py): torus / hypercube / K4,4 closed forms, the
- * 3x3x3-torus flow value 1/9 of Sec. 5.1, flow-conservation and level-cut
- * invariants, exact brute-force path enumeration for N <= 12.
+ * Pins (tests/test_oracle_*.py, tests/test_capacities.py, tests/test_demands.py): torus / hypercube /
+ * K4,4 closed forms, the 3x3x3-torus flow value 1/9 of Sec. 5.1, flow-conservation and level-cut
+ * invariants, exact brute-force path enumeration for N <= 12 (with unit and with unequal demands).
  */
 #include <pthread.h>
 #include <stdint.h>
@@ -194,6 +194,64 @@ int a2a_oracle_run(int32_t N, const int32_t* row_ptr, const int32_t* col, int32_
   if (flags) *flags = fl;
   free(jobs);
   free(tid);
+  return rc;
+}
+
+/*
+ * Link loads for commodities of unequal demand.  The paper's commodities all have the same
+ * demand (Sec. 3.1.1); here commodity (s,t) carries demand[(s - src_begin) * N + t] >= 0, split
+ * equally over its shortest paths as before (Sec. 5.2), so that
+ *   load[a] = sum_{s,t != s} demand(s,t) * (#shortest s->t paths through a) / sigma(s,t).
+ * In the dependency recursion the demand takes the place of the unit that every target
+ * contributes: the traffic over link (u,w) on behalf of source s is
+ * sigma(s,u)/sigma(s,w) * (demand(s,w) + delta(s,w)).  demand(s,s) and the demand of pairs
+ * without a path are ignored.  *weighted_dist = sum_{s,t} demand(s,t) * D(s,t) over reachable
+ * pairs, the link-time the demands need at least (the quantity that replaces sum D in the
+ * capacity argument of Theorem 1).  Serial, sources in ascending order.
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int a2a_oracle_run_demand(int32_t N, const int32_t* row_ptr, const int32_t* col, int32_t src_begin,
+                          int32_t src_count, const double* demand, double* load,
+                          double* weighted_dist) {
+  if (N <= 0 || !row_ptr || !demand || !load || src_begin < 0 || src_count < 0 ||
+      src_begin + (int64_t)src_count > N)
+    return -1;
+  int64_t E = row_ptr[N];
+  if (E > 0 && !col) return -1;
+  src_scratch sc;
+  sc.dist = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  sc.sigma = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)N);
+  sc.delta = (double*)malloc(sizeof(double) * (size_t)N);
+  sc.order = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  int rc = (!sc.dist || !sc.sigma || !sc.delta || !sc.order) ? -1 : 0;
+  double wd = 0.0;
+  if (rc == 0) {
+    memset(load, 0, sizeof(double) * (size_t)E);
+    for (int32_t s = src_begin; s < src_begin + src_count; ++s) {
+      const double* dem = demand + (size_t)(s - src_begin) * (size_t)N;
+      int64_t reached = 0;
+      int overflow = 0;
+      /* distances, path counts and the BFS order; no loads yet */
+      (void)one_source(N, row_ptr, col, s, &sc, NULL, &reached, &overflow);
+      for (int32_t i = (int32_t)reached; i >= 0; --i) {
+        int32_t u = sc.order[i];
+        if (u != s) wd += dem[u] * (double)sc.dist[u];
+        for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) {
+          int32_t w = col[a];
+          if (sc.dist[w] == sc.dist[u] + 1) {
+            double c = (double)sc.sigma[u] / (double)sc.sigma[w] * (dem[w] + sc.delta[w]);
+            load[a] += c;
+            sc.delta[u] += c;
+          }
+        }
+      }
+    }
+  }
+  if (weighted_dist) *weighted_dist = wd;
+  free(sc.dist);
+  free(sc.sigma);
+  free(sc.delta);
+  free(sc.order);
   return rc;
 }
 

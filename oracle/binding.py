@@ -51,6 +51,10 @@ def _load():
         lib.a2a_oracle_bound_cap.argtypes = [
             ctypes.c_int32, i32p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_double,
             ctypes.c_double, ctypes.c_void_p]
+        lib.a2a_oracle_run_demand.restype = ctypes.c_int
+        lib.a2a_oracle_run_demand.argtypes = [
+            ctypes.c_int32, i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.POINTER(ctypes.c_double)]
         lib.a2a_oracle_tree_sum.restype = ctypes.c_int64
         lib.a2a_oracle_tree_sum.argtypes = [ctypes.c_int32, ctypes.c_int32]
         _lib = lib
@@ -142,3 +146,21 @@ def tree_sum(N: int, d: int) -> int:
     if v < 0:
         raise ValueError("a2a_oracle_tree_sum rejected its arguments")
     return v
+
+
+def run_demand(row_ptr, col_idx, demand, src_begin: int = 0):
+    """Link loads and demand-weighted distance sum for demand[s - src_begin][t] (one row per source)."""
+    lib = _load()
+    row_ptr, rp = _i32(row_ptr)
+    col_idx, cp = _i32(col_idx)
+    N = len(row_ptr) - 1
+    demand = np.ascontiguousarray(demand, dtype=np.float64)
+    if demand.ndim != 2 or demand.shape[1] != N:
+        raise ValueError("demand must be [src_count][N]")
+    load = np.empty(int(row_ptr[-1]), dtype=np.float64)
+    wd = ctypes.c_double(0.0)
+    rc = lib.a2a_oracle_run_demand(N, rp, cp, int(src_begin), int(demand.shape[0]), demand.ctypes.data,
+                                   load.ctypes.data, ctypes.byref(wd))
+    if rc != 0:
+        raise ValueError("a2a_oracle_run_demand rejected its arguments")
+    return load, wd.value
