@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-distances", action="store_true",
                     help="skip the a2a_distances leg (distance matrix only, reported beside the metric)")
+    ap.add_argument("--no-demand", action="store_true",
+                    help="skip the a2a_link_loads_demand leg (unequal demands, reported beside the metric)")
     ap.add_argument("--max-workspace-gib", type=float, default=None)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 "
@@ -178,6 +180,33 @@ def main():
         "per_kernel": per_kernel,
     }
 
+    # the same path with a demand per pair (seeded uniform [0.5, 1.5), one double per pair), beside the metric
+    dem_leg = None
+    if not args.no_demand:
+        gen_dev = torch.Generator(device="cuda")
+        gen_dev.manual_seed(2024)
+        dem = torch.rand((N, N), generator=gen_dev, dtype=torch.float64, device="cuda").add_(0.5)  # [target][source]
+        dload = torch.empty(E, dtype=torch.float64, device="cuda")
+        wdist = torch.zeros(1, dtype=torch.float64, device="cuda")
+
+        def demstep():
+            topo.link_loads_demand(0, N, demand=dem, load=dload, weighted_dist=wdist, workspace=ws)
+
+        demstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            demstep()
+        torch.cuda.synchronize()
+        dmsec = (time.perf_counter() - t0) / args.steps
+        # every unit of demand crosses D(s,t) links: the loads must add up to demand x distance
+        total, wd = float(dload.sum().item()), float(wdist.item())
+        dem_leg = {"ms_per_step": dmsec * 1e3, "teps": N * E / dmsec, "unit": "edges/s",
+                   "extra_alg_bytes": 8.0 * N * N, "sum_load_over_weighted_dist": total / wd if wd else None,
+                   "what": "a2a_link_loads_demand over all sources, demand matrix double[N][N] resident in HBM"}
+        assert wd > 0 and abs(total / wd - 1.0) < 1e-9, (total, wd)
+        del dem, dload
+
     # a2a_distances alone (BFS + the int32 distance matrix), reported beside the metric
     dist_leg = None
     ws_gib = ws.numel() / 2 ** 30
@@ -247,6 +276,7 @@ def main():
         "topo_create_ms": t_create * 1e3,
         "roofline": roofline,
         "distances": dist_leg,
+        "demand": dem_leg,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

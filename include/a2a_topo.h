@@ -125,6 +125,29 @@ int a2a_link_loads(const a2a_topo* topo, int32_t src_begin, int32_t src_count, d
                    int64_t* dist_sum_total, int64_t* flags, void* workspace,
                    size_t workspace_bytes, void* hip_stream);
 
+/*
+ * The same for commodities of unequal demand.  The paper's commodities all have the same
+ * demand (Sec. 3.1.1); here the pair (s,t) carries demand(s,t), split equally over its
+ * shortest paths as before (Sec. 5.2):
+ *   load[a] = sum_s sum_{t != s} demand(s,t) * (# shortest s->t paths through link a) / sigma(s,t),
+ * i.e. demand(s,t) takes the place of the unit that target t contributes in the dependency
+ * recursion of a2a_link_loads.  Divide by link capacities with a2a_schedule_bound_cap.
+ *   demand          device, double[N][src_count], by target: demand[t * src_count + (s - src_begin)]
+ *                   is what source s sends to node t (the 64 sources of a batch lie next to each
+ *                   other).  Expected finite and >= 0, not checked; demand(s,s) and the demand of
+ *                   pairs without a path are ignored.  Read only.
+ *   load            device, double[E], overwritten
+ *   weighted_dist   device, double[1]: sum over reachable pairs of demand(s,t) * D(s,t), the
+ *                   link-time the demands need at least (what sum D is for unit demands in the
+ *                   capacity argument of Theorem 1).  May be NULL.
+ *   dist_sum_total, flags, workspace, stream: as for a2a_link_loads (same workspace size).
+ * Reproducible like a2a_link_loads.  A2A_ERR_INVALID_ARG for demand == NULL.
+ */
+int a2a_link_loads_demand(const a2a_topo* topo, int32_t src_begin, int32_t src_count,
+                          const double* demand, double* load, double* weighted_dist,
+                          int64_t* dist_sum_total, int64_t* flags, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
 typedef struct a2a_bound {
   double max_load;         /* Lmax: all-to-all time under unit demand and capacity (Sec. 5.3) */
   int64_t argmax_arc;      /* lowest link id whose load equals max_load */

@@ -37,7 +37,7 @@ FLAG_UNREACHABLE = 0x2
 
 EXPORTED_SYMBOLS = (
     "a2a_topo_create", "a2a_topo_destroy", "a2a_topo_info", "a2a_workspace_bytes",
-    "a2a_distances", "a2a_link_loads", "a2a_schedule_bound", "a2a_status_string",
+    "a2a_distances", "a2a_link_loads", "a2a_link_loads_demand", "a2a_schedule_bound", "a2a_status_string",
     "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound", "a2a_schedule_bound_cap",
 )
 
@@ -155,6 +155,8 @@ def load_library():
     lib.a2a_distances.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.a2a_link_loads.restype = ctypes.c_int
     lib.a2a_link_loads.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.a2a_link_loads_demand.restype = ctypes.c_int
+    lib.a2a_link_loads_demand.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.a2a_schedule_bound_cap.restype = ctypes.c_int
     lib.a2a_schedule_bound_cap.argtypes = [vp, vp, vp, i64, i64, ctypes.c_double, ctypes.c_double, vp, vp]
     lib.a2a_schedule_bound.restype = ctypes.c_int
@@ -248,6 +250,14 @@ class Topology:
             self._h, src_begin, src_count, _ptr(load), _ptr(dist_sum_total), _ptr(flags),
             _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream)),
             "a2a_link_loads")
+
+    def link_loads_demand(self, src_begin: int, src_count: int, *, demand, load, weighted_dist=None,
+                          dist_sum_total=None, flags=None, workspace, stream=None) -> int:
+        """``demand``: device float64 [N][src_count], ``demand[t][s - src_begin]`` = what s sends to t."""
+        return _check(load_library().a2a_link_loads_demand(
+            self._h, src_begin, src_count, _ptr(demand), _ptr(load), _ptr(weighted_dist), _ptr(dist_sum_total),
+            _ptr(flags), _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream)),
+            "a2a_link_loads_demand")
 
     def profile_enable(self, mode: int = 1) -> None:
         """0 off, 1 per-launch events, 2 events + count of shortest-path (source, link) pairs."""

@@ -268,7 +268,32 @@ struct GroupView {
   int N, Npad, Lcap, G, SB, bpb, nb64, inflight;
   int src_begin, src_count, batch0;
   int f32_levels;     // >= 1
+  // Commodities of unequal demand (nullptr: every pair has demand 1): demand of source
+  // src_begin + j to node t at dem[t * dem_ld + j], and per (batch, 64-node block) the sum of
+  // demand x distance over the pairs the backward pass has visited.
+  const double* dem;
+  long long dem_ld;
+  double* wpart;      // [G][nb64]
 };
+
+// The demands of one batch's sources: row t = node t, entry j = source j of the batch.
+__device__ __forceinline__ const double* demand_rows(const GroupView& gv, int g) {
+  return gv.dem + (size_t)(gv.batch0 + g) * 64;
+}
+
+// Sum over the lanes, the same in every lane and from run to run.
+__device__ __forceinline__ double wave_sum_double(double x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+  return x;
+}
+
+// Adds level x (a wave's sum of the demands it met) to its (batch, block) slot.
+__device__ __forceinline__ void add_weighted_dist(const GroupView& gv, int g, int u0, int level, double lane_sum) {
+  const double tot = wave_sum_double(lane_sum);
+  if (lane_id() == 0 && tot != 0.0) gv.wpart[(size_t)g * gv.nb64 + u0 / kWave] += (double)level * tot;
+}
+
 
 // The batch's sigma array of the given precision.
 template <typename T>
@@ -627,6 +652,17 @@ __device__ __forceinline__ double link_sums(double (&x)[8], const uint64_t (&m)[
 }
 
 // Own sigma of a node (1 in lanes that are not on this level), requested together with the rows.
+// Demand of the node's sources (a lane each; 1 where the lane is not on this level or all demands are 1).
+template <bool kDemand>
+__device__ __forceinline__ double own_demand(const double* __restrict__ dem, long long ld, int u0, const NodeIdx& me,
+                                             int node, int lane) {
+  double d = 1.0;
+  if constexpr (kDemand) {
+    if (lane_in(readlane64(me.mask, node))) d = dem[(size_t)(u0 + node) * (size_t)ld + lane];
+  }
+  return d;
+}
+
 template <typename TS>
 __device__ __forceinline__ TS own_sigma(const TS* __restrict__ dat, const NodeIdx& me, int node) {
   const uint64_t mu = readlane64(me.mask, node);
@@ -640,8 +676,8 @@ __device__ __forceinline__ TS own_sigma(const TS* __restrict__ dat, const NodeId
 // the link loads are made of); `add`: further round of a node with more than eight links.
 template <typename TS>
 __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const NodeIdx& me, int node, int i, TS sigma,
-                                             double (&x)[8], const uint64_t (&m)[8], int pairs, bool add, int lane,
-                                             double tot_l, double* sum8_buf) {
+                                             double dem, double (&x)[8], const uint64_t (&m)[8], int pairs, bool add,
+                                             int lane, double tot_l, double* sum8_buf) {
   const double s = (double)hold(sigma);
   double a = 0.0;
 #pragma unroll
@@ -653,14 +689,14 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
   if (lane_in(mu)) {
     double& e = entry(cf, of + rank_in(mu));
-    e = add ? e + a : recip(s) + a;
+    e = add ? e + a : dem * recip(s) + a;
   }
   if (pairs != 0) tot_l = link_sums(x, m, pairs, i, lane, tot_l, sum8_buf);
   return tot_l;
 }
 
-// TS: precision in which this level keeps sigma.
-template <typename TS>
+// TS: precision in which this level keeps sigma.  kDemand: commodities of unequal demand.
+template <typename TS, bool kDemand>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
             int level) {
@@ -674,6 +710,8 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
+  double wd = 0.0;  // this lane's source: demands met
   __shared__ double s_sum8[kWavesPerBlock][kSum8Doubles];
   double* sum8_buf = s_sum8[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + u0 + lane);
@@ -699,17 +737,22 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
       uint64_t ma[8], mb[8];
       double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i
       TS sa = own_sigma(dat, me, 8 * c), sb;
+      double da = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c, lane), db;
       int pa = gather8(cf, tile, 0, readlane64(me.mask, 8 * c), xa, ma), pb;
 #pragma unroll 1
       for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
         sb = own_sigma(dat, me, 8 * c + i + 1);
+        db = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c + i + 1, lane);
         pb = gather8(cf, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, mb);
-        tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, false, lane, tot_l, sum8_buf);
+        tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, da, xa, ma, pa, false, lane, tot_l, sum8_buf);
+        if (kDemand && lane_in(readlane64(me.mask, 8 * c + i))) wd += da;
         if (i + 2 < 8) {
           sa = own_sigma(dat, me, 8 * c + i + 2);
+          da = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c + i + 2, lane);
           pa = gather8(cf, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, ma);
         }
-        tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, xb, mb, pb, false, lane, tot_l, sum8_buf);
+        tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, db, xb, mb, pb, false, lane, tot_l, sum8_buf);
+        if (kDemand && lane_in(readlane64(me.mask, 8 * c + i + 1))) wd += db;
       }
       const uint64_t mu_lane = shfl64(me.mask, 8 * c + (lane >> 3));
       if (q >= 0 && (tile.mask & mu_lane) != 0) unsafeAtomicAdd(&pt[q], tot_l);
@@ -724,7 +767,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
           pa = gather8(cf, extra, i, readlane64(me.mask, 8 * c + i), xa, ma);
           if (pa == 0) continue;
           sa = own_sigma(dat, me, 8 * c + i);
-          tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, xa, ma, pa, true, lane, tot_l, sum8_buf);
+          tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, 1.0, xa, ma, pa, true, lane, tot_l, sum8_buf);
         }
         if (qe >= 0 && (extra.mask & mu_lane) != 0) unsafeAtomicAdd(&pt[qe], tot_l);
       }
@@ -733,6 +776,7 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
     q = q_next;
     q_next = q_nn;
   }
+  if (kDemand) add_weighted_dist(gv, g, u0, level, wd);
 }
 
 // --- levels with few sources per node: one lane per (node, link) ---------------------------
@@ -765,15 +809,18 @@ __device__ __forceinline__ double bcast8(double x) {
 // The next (up to) eight sources of `rest`, lowest first: x[k] = the entry of the k-th of them in
 // the link's row (mk, ofk), 0 if the link does not carry it or there is no k-th source.  All
 // requests are issued before any value is used.
+// mine: the source that this lane's place among its eight lanes stands for (-1: none left).
 template <typename T>
 __device__ __forceinline__ void few_fetch8(const T* __restrict__ rows, uint64_t mk, uint32_t ofk, uint64_t& rest,
-                                           T (&x)[8]) {
+                                           T (&x)[8], int place, int& mine) {
+  mine = -1;
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
     x[k] = (T)0;
     if (rest != 0) {
       const int s = __builtin_ctzll(rest);
       rest &= rest - 1;
+      if (k == place) mine = s;
       if ((mk >> s) & 1ull) x[k] = entry(rows, ofk + below(mk, s));
     }
   }
@@ -790,7 +837,8 @@ __device__ __forceinline__ bool few_fwd(const TIn* __restrict__ rows, TOut* __re
   bool big = false;
   while (__ballot(rest != 0) != 0) {
     TIn xr[8];
-    few_fetch8(rows, tl.mask, tl.off, rest, xr);
+    int mine;
+    few_fetch8(rows, tl.mask, tl.off, rest, xr, lane & 7, mine);
     double x[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) x[k] = (double)hold(xr[k]);
@@ -808,18 +856,25 @@ __device__ __forceinline__ bool few_fwd(const TIn* __restrict__ rows, TOut* __re
 }
 
 // coef of the node's sources and this lane's link load from one tile of out-links.
+// dem_row (nullptr: all demands 1): the demands of this lane's node; wd collects the ones met.
 template <typename TS>
 __device__ __forceinline__ double few_bwd(const TS* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
-                                          uint64_t mu, uint32_t ofu, bool add, int lane) {
+                                          uint64_t mu, uint32_t ofu, bool add, int lane,
+                                          const double* __restrict__ dem_row, double& wd) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   int left = __popcll(mu) - (lane & 7);
   double acc = 0.0;
   while (__ballot(rest != 0) != 0) {
     double x[8];
-    few_fetch8(cf, tl.mask, tl.off, rest, x);
+    int mine;
+    few_fetch8(cf, tl.mask, tl.off, rest, x, lane & 7, mine);
     TS sg_own = (TS)1;  // lane j: sigma of the node's j-th source of these eight
-    if (left > 0) sg_own = entry(dat, e);
+    double dm = 1.0;
+    if (left > 0) {
+      sg_own = entry(dat, e);
+      if (dem_row != nullptr && !add) dm = dem_row[mine];
+    }
     const double sg = (double)hold(sg_own);
     acc = __builtin_fma(bcast8<0>(sg), x[0], acc);
     acc = __builtin_fma(bcast8<1>(sg), x[1], acc);
@@ -831,9 +886,10 @@ __device__ __forceinline__ double few_bwd(const TS* __restrict__ dat, double* __
     acc = __builtin_fma(bcast8<7>(sg), x[7], acc);
     double a = group_sum8(x, lane);
     if (left > 0 && !(add && a == 0.0)) {
-      a += add ? entry(cf, e) : recip(sg);
+      a += add ? entry(cf, e) : dm * recip(sg);
       entry(cf, e) = a;
     }
+    if (dem_row != nullptr && !add && left > 0) wd += dm;
     e += 8;
     left -= 8;
   }
@@ -919,7 +975,8 @@ __device__ __forceinline__ bool slot_fwd(const TIn* __restrict__ rows, TOut* __r
 // Returns, in lane 8i+j, the load of link j of node i from this tile.
 template <typename TS>
 __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* __restrict__ cf, const Tile& tl,
-                                           uint64_t mu, uint32_t ofu, bool add, int lane) {
+                                           uint64_t mu, uint32_t ofu, bool add, int lane,
+                                           const double* __restrict__ dem_row, double& wd) {
   uint64_t rest = mu;
   uint32_t e = ofu + (uint32_t)(lane & 7);
   double p[8];
@@ -930,7 +987,11 @@ __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* _
     double x[8];
     slot_fetch8(cf, tl, s, x);
     TS sg_own = (TS)1;
-    if (s >= 0) sg_own = entry(dat, e);
+    double dm = 1.0;
+    if (s >= 0) {
+      sg_own = entry(dat, e);
+      if (dem_row != nullptr && !add) dm = dem_row[s];
+    }
     const double sg = (double)hold(sg_own);
     double a = 0.0;
 #pragma unroll
@@ -939,9 +1000,10 @@ __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* _
       p[j] = __builtin_fma(sg, x[j], p[j]);
     }
     if (s >= 0 && !(add && a == 0.0)) {
-      a += add ? entry(cf, e) : recip(sg);
+      a += add ? entry(cf, e) : dm * recip(sg);
       entry(cf, e) = a;
     }
+    if (dem_row != nullptr && !add && s >= 0) wd += dm;
     e += 8;
   }
   return group_sum8(p, lane);
@@ -1161,7 +1223,7 @@ __device__ __forceinline__ double spread_link_bwd(const double* __restrict__ row
   return tot;
 }
 
-template <typename TS>
+template <typename TS, bool kDemand>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
   int g, nblk;
@@ -1174,6 +1236,8 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
   const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
+  double wd = 0.0;
   __shared__ double s_acc[kWavesPerBlock][8][kWave], s_sig[kWavesPerBlock][8][kWave];  // [node of the tile][source]
   double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
   double(*sig)[kWave] = s_sig[threadIdx.x / kWave];
@@ -1197,12 +1261,14 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
     if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       TS sg_own[8];  // lane = source: sigma of the nodes' sources, all rows requested first
+      double dm[8];  // and their demands
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const uint64_t mu_i = readlane64(me.mask, 8 * c + i);
         const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
         sg_own[i] = (TS)1;
         if (lane_in(mu_i)) sg_own[i] = entry(dat, of + rank_in(mu_i));
+        dm[i] = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c + i, lane);
       }
       double sg[8];
 #pragma unroll
@@ -1229,7 +1295,10 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
       for (int i = 0; i < 8; ++i) {  // lane = source: the node's coef row
         const uint64_t mu_i = readlane64(me.mask, 8 * c + i);
         const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-        if (lane_in(mu_i)) entry(cf, of + rank_in(mu_i)) = recip(sg[i]) + acc[i][lane];
+        if (lane_in(mu_i)) {
+          entry(cf, of + rank_in(mu_i)) = dm[i] * recip(sg[i]) + acc[i][lane];
+          if (kDemand) wd += dm[i];
+        }
       }
       __builtin_amdgcn_wave_barrier();
     }
@@ -1237,9 +1306,10 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
     q = q_next;
     q_next = q_nn;
   }
+  if (kDemand) add_weighted_dist(gv, g, u0, level, wd);
 }
 
-template <bool kSlots, typename TS>
+template <bool kSlots, typename TS, bool kDemand>
 __global__ void __launch_bounds__(kBlock)
 k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
   int g, nblk;
@@ -1252,6 +1322,8 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
   const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
   double* __restrict__ cf = gv.coef + (size_t)g * gv.Npad * 64;
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
+  const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
+  double wd = 0.0;
   const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -1274,16 +1346,17 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
-      const double tot =
-          kSlots ? slot_bwd(dat, cf, tile, mu, ofu, false, lane) : few_bwd(dat, cf, tile, mu, ofu, false, lane);
+      const double* __restrict__ dem_row = kDemand ? dem + (size_t)(u0 + node) * (size_t)gv.dem_ld : nullptr;
+      const double tot = kSlots ? slot_bwd(dat, cf, tile, mu, ofu, false, lane, dem_row, wd)
+                                : few_bwd(dat, cf, tile, mu, ofu, false, lane, dem_row, wd);
       if (q >= 0 && (tile.mask & mu) != 0) unsafeAtomicAdd(&pt[q], tot);
       // nodes with more than eight out-links: add the rest to the stored coef
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         int qe;
         const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
-        const double te =
-            kSlots ? slot_bwd(dat, cf, extra, mu, ofu, true, lane) : few_bwd(dat, cf, extra, mu, ofu, true, lane);
+        const double te = kSlots ? slot_bwd(dat, cf, extra, mu, ofu, true, lane, dem_row, wd)
+                                 : few_bwd(dat, cf, extra, mu, ofu, true, lane, dem_row, wd);
         if (qe >= 0 && (extra.mask & mu) != 0) unsafeAtomicAdd(&pt[qe], te);
       }
     }
@@ -1291,6 +1364,7 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
     q = q_next;
     q_next = q_nn;
   }
+  if (kDemand) add_weighted_dist(gv, g, u0, level, wd);
 }
 
 // load[a] = (first group ? 0 : load[a]) + part[0][a] + part[1][a] + ... in that order.
@@ -1465,6 +1539,23 @@ k_fold_counters(GroupView gv, int depth, long long* __restrict__ misc) {
     misc[1] += s_r[0][0];
     misc[2] += s_r[1][0];
   }
+}
+
+// *out += wpart[0] + wpart[1] + ... : thread t adds the elements t, t + kBlock, ... in that order,
+// then the threads' sums are added in a fixed tree.
+__global__ void __launch_bounds__(kBlock)
+k_fold_weighted(const double* __restrict__ wpart, long long n, double* __restrict__ out) {
+  __shared__ double s_r[kBlock];
+  const int t = (int)threadIdx.x;
+  double x = 0.0;
+  for (long long i = t; i < n; i += kBlock) x += wpart[i];
+  s_r[t] = x;
+  __syncthreads();
+  for (int o = kBlock / 2; o > 0; o >>= 1) {
+    if (t < o) s_r[t] += s_r[t + o];
+    __syncthreads();
+  }
+  if (t == 0) out[0] += s_r[0];
 }
 
 // Final outputs of a call: totals and flag bits (bit 0: sigma reached 2^53, bit 1: some pair

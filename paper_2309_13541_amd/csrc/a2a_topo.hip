@@ -83,6 +83,7 @@ struct Layout {
                              // the same array: the single-precision levels come first, so the two never meet
   size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
   size_t off_part = 0;       // double [G][Epad]
+  size_t off_wpart = 0;      // double [G][nb64]  demand x distance per (batch, 64-node block)
   size_t total = 0;
 };
 
@@ -119,6 +120,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_dat = L.values ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
     const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
+    const size_t o_wpart = L.loads ? take((size_t)G * L.nb64 * 8) : 0;
     if (out) {
       out->off_level_new = o_level_new;
       out->off_misc = o_misc;
@@ -132,6 +134,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->off_dat = o_dat;
       out->off_coef = o_coef;
       out->off_part = o_part;
+      out->off_wpart = o_wpart;
       out->total = off;
       out->G = G;
     }
@@ -230,6 +233,7 @@ struct Run {
   char* ws;
   hipStream_t st;
   int src_begin, src_count;
+  const double* demand = nullptr;  // [N][src_count] by target, or nullptr: every pair has demand 1
   int inflight = kXcd;  // batches in flight = XCDs: one batch's node blocks per XCD at a time
   mutable std::vector<double> lanes_per_node;  // per level of the current group: pairs / (G*N)
   bool few(int level) const {
@@ -276,6 +280,9 @@ struct Run {
     gv.src_count = src_count;
     gv.batch0 = batch0;
     gv.f32_levels = f32_levels();
+    gv.dem = demand;
+    gv.dem_ld = src_count;
+    gv.wpart = L.loads ? (double*)(ws + L.off_wpart) : nullptr;
     return gv;
   }
 };
@@ -344,9 +351,12 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
   {
+    // With demands the backward pass also visits the deepest level and looks at the (empty) level
+    // after it, which the BFS has computed: its index entries are written too.
+    const int idx_depth = gv.dem != nullptr ? depth + 1 : depth;
     ProfScope ps(t, PROF_OFFSETS, r.st);
-    if (depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * depth), kWave, 0, r.st>>>(gv, depth);
-    k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, depth);
+    if (idx_depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * idx_depth), kWave, 0, r.st>>>(gv, idx_depth);
+    k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, idx_depth);
   }
   const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
@@ -354,7 +364,7 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     ProfScope ps(t, few ? PROF_FWD_FEW : (spread ? PROF_FWD_SPREAD : PROF_FWD), r.st, l);
     const bool count = t->prof_mode == 2;
     // the deepest level's coef is 1/sigma: the forward launch leaves it there
-    const bool init_coef = gv.coef != nullptr && l == depth;
+    const bool init_coef = gv.coef != nullptr && l == depth && gv.dem == nullptr;
     auto launch = [&](auto kernel) {
       kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
     };
@@ -578,13 +588,17 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
   return A2A_OK;
 }
 
-int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, double* load,
-                   int64_t* dist_sum_total, int64_t* flags, void* workspace, size_t workspace_bytes,
-                   void* hip_stream) {
+namespace {
+
+// a2a_link_loads (demand == nullptr) and a2a_link_loads_demand.
+int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const double* demand, double* load,
+               double* weighted_dist, int64_t* dist_sum_total, int64_t* flags, void* workspace,
+               size_t workspace_bytes, void* hip_stream) {
   int rc = check_common(t, src_begin, src_count, workspace);
   if (rc != A2A_OK) return rc;
   if (!load && t->E > 0) return A2A_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
+  if (weighted_dist) HIP_TRY(hipMemsetAsync(weighted_dist, 0, 8, st));
   if (src_count == 0) {
     if (t->E > 0) HIP_TRY(hipMemsetAsync(load, 0, (size_t)t->E * 8, st));
     if (dist_sum_total) HIP_TRY(hipMemsetAsync(dist_sum_total, 0, 8, st));
@@ -599,6 +613,7 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
   r.st = st;
   r.src_begin = src_begin;
   r.src_count = src_count;
+  r.demand = demand;
   const Layout& L = r.L;
   HIP_TRY(hipMemsetAsync(r.misc(), 0, 64, st));
   const int nb = (src_count + 63) / 64;
@@ -611,27 +626,33 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
     if (rc != A2A_OK) return rc;
     if (t->E > 0) {
       HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
+      if (demand) HIP_TRY(hipMemsetAsync(gv.wpart, 0, (size_t)gv.G * L.nb64 * 8, st));
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
-      for (int l = depth - 1; l >= 0; --l) {  // the deepest level has no successors: nothing to add
+      // Unit demands: the deepest level has no successors and its coef = 1/sigma was left by the
+      // forward pass, nothing to add.  With demands it is visited like the others.
+      for (int l = demand ? depth : depth - 1; l >= 0; --l) {
         const bool spread = r.bwd_spread(l, depth);
         ProfScope ps(t, r.few(l) ? PROF_BWD_FEW : (spread ? PROF_BWD_SPREAD : PROF_BWD), st, l);
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
-        auto pick = [&](auto ts) {  // precision of this level's sigma
+        auto pick = [&](auto ts, auto with_demand) {  // precision of this level's sigma
           using TS = decltype(ts);
+          constexpr bool kDemand = decltype(with_demand)::value;
           if (spread)
-            launch(k_bwd_spread<TS>);
+            launch(k_bwd_spread<TS, kDemand>);
           else if (!r.few(l))
-            launch(k_bwd_level<TS>);
+            launch(k_bwd_level<TS, kDemand>);
           else if (r.slots(l))
-            launch(k_bwd_few<true, TS>);
+            launch(k_bwd_few<true, TS, kDemand>);
           else
-            launch(k_bwd_few<false, TS>);
+            launch(k_bwd_few<false, TS, kDemand>);
         };
-        if (r.narrow(l))
-          pick(float{});
+        if (demand)
+          r.narrow(l) ? pick(float{}, std::true_type{}) : pick(double{}, std::true_type{});
         else
-          pick(double{});
+          r.narrow(l) ? pick(float{}, std::false_type{}) : pick(double{}, std::false_type{});
       }
+      if (demand && weighted_dist)
+        k_fold_weighted<<<1, kBlock, 0, st>>>(gv.wpart, (long long)gv.G * L.nb64, weighted_dist);
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(
           gv.part, L.Epad, gv.G, (long long)t->E, b0 == 0 ? 1 : 0, load);
@@ -644,6 +665,23 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
   HIP_TRY(hipGetLastError());
   t->prof_calls++;
   return A2A_OK;
+}
+
+}  // namespace
+
+int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, double* load,
+                   int64_t* dist_sum_total, int64_t* flags, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+  return link_loads(t, src_begin, src_count, nullptr, load, nullptr, dist_sum_total, flags, workspace,
+                    workspace_bytes, hip_stream);
+}
+
+int a2a_link_loads_demand(const a2a_topo* t, int32_t src_begin, int32_t src_count, const double* demand,
+                          double* load, double* weighted_dist, int64_t* dist_sum_total, int64_t* flags,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!demand) return A2A_ERR_INVALID_ARG;
+  return link_loads(t, src_begin, src_count, demand, load, weighted_dist, dist_sum_total, flags, workspace,
+                    workspace_bytes, hip_stream);
 }
 
 int a2a_schedule_bound(const a2a_topo* t, const double* load, int64_t sum_dist, int64_t flags,

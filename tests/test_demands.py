@@ -132,3 +132,115 @@ def test_partial_source_range_and_bad_arguments(oracle):
         oracle.run_demand(rp, col, dem[:, :5])
     with pytest.raises(ValueError):
         oracle.run_demand(rp, col, dem, 3)  # 3 + 16 sources > N
+
+
+# ---------------------------------------------------------------------------------------------------------
+# GPU: a2a_link_loads_demand against the oracle
+# ---------------------------------------------------------------------------------------------------------
+
+def run_demand_gpu(topo, dem_by_source, src_begin=0, max_ws=None):
+    """dem_by_source: numpy [src_count][N] (the oracle's layout); the library takes it by target."""
+    import torch
+    import paper_2309_13541_amd as a2a
+    cnt = dem_by_source.shape[0]
+    ws = topo.alloc_workspace(cnt, a2a.WS_LOADS, max_ws)
+    dem = torch.from_numpy(np.ascontiguousarray(dem_by_source.T)).cuda()  # [N][src_count]
+    load = torch.full((max(topo.E, 1),), -7.0, dtype=torch.float64, device="cuda")
+    wd = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    dsum = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    flags = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    topo.link_loads_demand(src_begin, cnt, demand=dem, load=load, weighted_dist=wd, dist_sum_total=dsum,
+                           flags=flags, workspace=ws)
+    torch.cuda.synchronize()
+    return load[:topo.E].cpu().numpy(), float(wd.item()), int(dsum.item()), int(flags.item())
+
+
+def _gpu_cases():
+    from test_gpu_parity import SMALL, FUNNELS, funnel_layers
+    cases = [(n, SMALL[n], None) for n in sorted(SMALL) if len(SMALL[n][1]) and n not in ("chain_2pow54",)]
+    cases += [(n, funnel_layers(*FUNNELS[n]), 64) for n in sorted(FUNNELS)]
+    cases += [("C1", gen.named_config("C1"), None), ("C2", gen.named_config("C2"), None)]
+    return cases
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", _gpu_cases(), ids=lambda c: c[0])
+def test_gpu_demand_loads_match_oracle(oracle, case):
+    """Every kernel flavour with demands (the graphs are those of the flavour test of test_gpu_parity)."""
+    import paper_2309_13541_amd as a2a
+    from gpu_helpers import assert_loads_close
+    name, (rp, col), cnt = case
+    N = len(rp) - 1
+    cnt = N if cnt is None else cnt
+    print(f"case {name} N={N} E={len(col)} sources={cnt}", flush=True)
+    dem = seeded_demand(cnt, N, 1000 + N)
+    want, want_wd = oracle.run_demand(rp, col, dem)
+    ref = oracle.run(rp, col, 0, cnt)
+    topo = a2a.Topology(rp, col)
+    load, wd, dsum, flags = run_demand_gpu(topo, dem)
+    assert_loads_close(load, want)
+    assert wd == pytest.approx(want_wd, rel=1e-12)
+    assert dsum == int(ref.dist_sum.sum()) and flags == ref.flags
+    topo.close()
+
+
+@pytest.mark.gpu
+def test_gpu_unit_demand_matrix_gives_the_unit_loads(oracle):
+    from gpu_helpers import run_link_loads
+    import paper_2309_13541_amd as a2a
+    for rp, col in (gen.random_regular(300, 4, 5), gen.torus([5, 13])):
+        N = len(rp) - 1
+        topo = a2a.Topology(rp, col)
+        unit, dsum, _ = run_link_loads(topo)
+        load, wd, dsum2, _ = run_demand_gpu(topo, np.ones((N, N)))
+        # same sums in the same order, except that the deepest level is visited by the backward kernel
+        np.testing.assert_allclose(load, unit, rtol=1e-13)
+        assert wd == float(dsum) and dsum2 == dsum
+        topo.close()
+
+
+@pytest.mark.gpu
+def test_gpu_demand_source_ranges_groups_and_reruns(oracle):
+    import paper_2309_13541_amd as a2a
+    from gpu_helpers import assert_loads_close
+    rp, col = gen.random_regular(1000, 6, 21)
+    N = 1000
+    topo = a2a.Topology(rp, col)
+    dem = seeded_demand(N, N, 9)
+    want, want_wd = oracle.run_demand(rp, col, dem)
+    full = run_demand_gpu(topo, dem)
+    assert_loads_close(full[0], want)
+    assert full[1] == pytest.approx(want_wd, rel=1e-12)
+    again = run_demand_gpu(topo, dem)
+    assert np.array_equal(full[0], again[0]) and full[1] == again[1]  # run-to-run bitwise
+    least = topo.workspace_bytes(N, a2a.WS_LOADS | a2a.WS_MINIMAL)
+    small = run_demand_gpu(topo, dem, max_ws=least)  # one super-batch at a time: several groups
+    np.testing.assert_allclose(small[0], full[0], rtol=1e-12)
+    assert small[1] == pytest.approx(full[1], rel=1e-13)
+    # a source range that starts and ends inside a batch
+    part, part_wd = oracle.run_demand(rp, col, dem[70:203], 70)
+    got = run_demand_gpu(topo, dem[70:203], 70)
+    assert_loads_close(got[0], part)
+    assert got[1] == pytest.approx(part_wd, rel=1e-12)
+    topo.close()
+
+
+@pytest.mark.gpu
+def test_gpu_demand_argument_checks():
+    import torch
+    import paper_2309_13541_amd as a2a
+    rp, col = gen.torus([4, 4])
+    topo = a2a.Topology(rp, col)
+    ws = topo.alloc_workspace(16, a2a.WS_LOADS)
+    load = torch.zeros(topo.E, dtype=torch.float64, device="cuda")
+    with pytest.raises(a2a.A2AError) as e:
+        topo.link_loads_demand(0, 16, demand=None, load=load, workspace=ws)
+    assert e.value.status == a2a.ERR_INVALID_ARG
+    # no sources: zero loads and zero weighted distance
+    wd = torch.full((1,), 5.0, dtype=torch.float64, device="cuda")
+    dem = torch.ones((16, 1), dtype=torch.float64, device="cuda")
+    load.fill_(3.0)
+    topo.link_loads_demand(4, 0, demand=dem, load=load, weighted_dist=wd, workspace=ws)
+    torch.cuda.synchronize()
+    assert float(wd.item()) == 0.0 and float(load.abs().sum().item()) == 0.0
+    topo.close()
