@@ -1507,6 +1507,13 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
 // bookkeeping
 // ---------------------------------------------------------------------------------------
 
+// p[0..n) = 0, eight bytes per thread and step.  Used instead of the runtime's memset so that a
+// call only ever enqueues kernels of this library on the caller's stream.
+__global__ void __launch_bounds__(kBlock) k_zero(unsigned long long* __restrict__ p, size_t n) {
+  const size_t stride = (size_t)gridDim.x * kBlock;
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) p[i] = 0ull;
+}
+
 // Folds the per-batch level totals of a finished group into the call's running totals:
 // misc[1] += sum of distances, misc[2] += reached pairs.  One workgroup; integer sums, so the
 // order does not matter.

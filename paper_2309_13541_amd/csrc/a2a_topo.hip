@@ -167,6 +167,16 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     }                           \
   } while (0)
 
+// Zeroes `bytes` bytes (rounded up to a multiple of 8; every array it is used on has that room) at
+// the 8-byte aligned device address p with a kernel on the stream.
+inline hipError_t zero_async(void* p, size_t bytes, hipStream_t st) {
+  const size_t n = (bytes + 7) / 8;
+  if (n == 0) return hipSuccess;
+  const size_t blocks = (n + kBlock - 1) / kBlock;
+  k_zero<<<(unsigned)(blocks < 16384 ? blocks : 16384), kBlock, 0, st>>>((unsigned long long*)p, n);
+  return hipGetLastError();
+}
+
 // Brackets one kernel launch with two events while profiling is on.
 struct ProfScope {
   const a2a_topo* t;
@@ -291,8 +301,8 @@ struct Run {
 int run_bfs(const Run& r, const GroupView& gv, int* depth) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
-  HIP_TRY(hipMemsetAsync(r.level_new(), 0, (size_t)L.Lcap * 4, r.st));
-  HIP_TRY(hipMemsetAsync(gv.ltot, 0, (size_t)gv.SB * kSub * L.Lcap * 8, r.st));
+  HIP_TRY(zero_async(r.level_new(), (size_t)L.Lcap * 4, r.st));
+  HIP_TRY(zero_async(gv.ltot, (size_t)gv.SB * kSub * L.Lcap * 8, r.st));
   {
     ProfScope ps(t, PROF_INIT, r.st);
     k_init_group<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv);
@@ -539,8 +549,8 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
   if (rc != A2A_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   if (src_count == 0) {
-    if (unreachable) HIP_TRY(hipMemsetAsync(unreachable, 0, 8, st));
-    if (flags) HIP_TRY(hipMemsetAsync(flags, 0, 8, st));
+    if (unreachable) HIP_TRY(zero_async(unreachable, 8, st));
+    if (flags) HIP_TRY(zero_async(flags, 8, st));
     return A2A_OK;
   }
   Run r;
@@ -552,8 +562,8 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
   r.src_begin = src_begin;
   r.src_count = src_count;
   const Layout& L = r.L;
-  HIP_TRY(hipMemsetAsync(r.misc(), 0, 64, st));
-  if (dist_sum) HIP_TRY(hipMemsetAsync(dist_sum, 0, (size_t)src_count * 8, st));
+  HIP_TRY(zero_async(r.misc(), 64, st));
+  if (dist_sum) HIP_TRY(zero_async(dist_sum, (size_t)src_count * 8, st));
   const int nb = (src_count + 63) / 64;
   const int tiles = L.Npad / kWave;
   for (int b0 = 0; b0 < nb; b0 += L.G) {
@@ -598,11 +608,11 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
   if (rc != A2A_OK) return rc;
   if (!load && t->E > 0) return A2A_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (weighted_dist) HIP_TRY(hipMemsetAsync(weighted_dist, 0, 8, st));
+  if (weighted_dist) HIP_TRY(zero_async(weighted_dist, 8, st));
   if (src_count == 0) {
-    if (t->E > 0) HIP_TRY(hipMemsetAsync(load, 0, (size_t)t->E * 8, st));
-    if (dist_sum_total) HIP_TRY(hipMemsetAsync(dist_sum_total, 0, 8, st));
-    if (flags) HIP_TRY(hipMemsetAsync(flags, 0, 8, st));
+    if (t->E > 0) HIP_TRY(zero_async(load, (size_t)t->E * 8, st));
+    if (dist_sum_total) HIP_TRY(zero_async(dist_sum_total, 8, st));
+    if (flags) HIP_TRY(zero_async(flags, 8, st));
     return A2A_OK;
   }
   Run r;
@@ -615,7 +625,7 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
   r.src_count = src_count;
   r.demand = demand;
   const Layout& L = r.L;
-  HIP_TRY(hipMemsetAsync(r.misc(), 0, 64, st));
+  HIP_TRY(zero_async(r.misc(), 64, st));
   const int nb = (src_count + 63) / 64;
   for (int b0 = 0; b0 < nb; b0 += L.G) {
     const GroupView gv = r.view(b0, nb - b0 < L.G ? nb - b0 : L.G);
@@ -625,8 +635,8 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
     rc = run_fwd(r, gv, depth);
     if (rc != A2A_OK) return rc;
     if (t->E > 0) {
-      HIP_TRY(hipMemsetAsync(gv.part, 0, (size_t)gv.G * L.Epad * 8, st));
-      if (demand) HIP_TRY(hipMemsetAsync(gv.wpart, 0, (size_t)gv.G * L.nb64 * 8, st));
+      HIP_TRY(zero_async(gv.part, (size_t)gv.G * L.Epad * 8, st));
+      if (demand) HIP_TRY(zero_async(gv.wpart, (size_t)gv.G * L.nb64 * 8, st));
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
       // Unit demands: the deepest level has no successors and its coef = 1/sigma was left by the
       // forward pass, nothing to add.  With demands it is visited like the others.

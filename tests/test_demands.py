@@ -184,6 +184,49 @@ def test_gpu_demand_loads_match_oracle(oracle, case):
     topo.close()
 
 
+def big_demand(n_src, N, seed):
+    """Whole-number demands 0..7 (one in eight zero) from numpy's seeded generator: an input, drawn once and
+    handed to both sides."""
+    return np.random.default_rng(seed).integers(0, 8, size=(n_src, N)).astype(np.float64)
+
+
+def oracle_demand_sliced(oracle, rp, col, dem, src_begin, slices=16):
+    """The serial oracle on consecutive slices of the sources, one thread each (the C call releases the
+    interpreter lock); loads and weighted distances of the slices added in source order."""
+    from concurrent.futures import ThreadPoolExecutor
+    cnt = dem.shape[0]
+    cuts = [cnt * i // slices for i in range(slices + 1)]
+    jobs = [(a, b) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    with ThreadPoolExecutor(max_workers=len(jobs)) as ex:
+        parts = list(ex.map(lambda ab: oracle.run_demand(rp, col, dem[ab[0]:ab[1]], src_begin + ab[0]), jobs))
+    load = np.zeros(len(col))
+    wd = 0.0
+    for l, w in parts:
+        load += l
+        wd += w
+    return load, wd
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,s0,cnt", [("C3", 0, 4096), ("C4", 0, 16384), ("C5", 20000, 640)])
+def test_gpu_demand_loads_at_config_size(oracle, name, s0, cnt):
+    """Unequal demands at the size of the benchmark configurations, link by link: C3 and C4 over all sources,
+    C5 over ten batches of sources."""
+    import paper_2309_13541_amd as a2a
+    from gpu_helpers import assert_loads_close
+    rp, col = gen.named_config(name)
+    N = len(rp) - 1
+    print(f"case {name} N={N} E={len(col)} sources {s0}+{cnt}", flush=True)
+    dem = big_demand(cnt, N, 4000 + N)
+    want, want_wd = oracle_demand_sliced(oracle, rp, col, dem, s0)
+    topo = a2a.Topology(rp, col)
+    load, wd, dsum, flags = run_demand_gpu(topo, dem, s0)
+    assert flags == 0
+    assert_loads_close(load, want)
+    assert wd == pytest.approx(want_wd, rel=1e-12)
+    topo.close()
+
+
 @pytest.mark.gpu
 def test_gpu_unit_demand_matrix_gives_the_unit_loads(oracle):
     from gpu_helpers import run_link_loads

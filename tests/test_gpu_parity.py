@@ -227,15 +227,34 @@ def test_c5_source_ranges_loads(a2a, oracle):
     topo.close()
 
 
-def test_c5_full_against_stored_oracle_values(a2a, oracle):
-    """Full C5 in the benchmark's launch configuration (recommended workspace): stored oracle
-    figures (sum of distances, extrema, 257 sampled links) plus the load-sum invariant."""
-    with open(os.path.join(GOLDEN, "oracle_config_values.json")) as f:
-        g = json.load(f)["C5"]
+@pytest.fixture(scope="module")
+def c5_full(a2a):
+    """One full C5 run in the benchmark's launch configuration (recommended workspace, all 1024 batches in
+    one group), shared by the tests below."""
     rp, col = gen.named_config("C5")
     topo = a2a.Topology(rp, col)
     print("case C5 full", flush=True)
     load, dtot, flags = run_link_loads(topo)
+    yield rp, col, topo, load, dtot, flags
+    topo.close()
+
+
+def test_c5_full_loads_element_by_element(c5_full, oracle):
+    """All 524 283 link loads of the full 65 536-source run against a live oracle run, link by link."""
+    rp, col, topo, load, dtot, flags = c5_full
+    o = oracle.run(rp, col, threads=16)
+    assert flags == o.flags == 0 and o.unreachable == 0
+    assert dtot == int(o.dist_sum.sum())
+    assert_loads_close(load, o.load)
+    assert int(np.argmax(load)) == int(np.argmax(o.load))
+
+
+def test_c5_full_against_stored_oracle_values(c5_full, oracle):
+    """The same run against the stored oracle figures (sum of distances, extrema, 257 sampled links) and
+    the load-sum invariant."""
+    with open(os.path.join(GOLDEN, "oracle_config_values.json")) as f:
+        g = json.load(f)["C5"]
+    rp, col, topo, load, dtot, flags = c5_full
     assert dtot == g["sum_dist"] and flags == 0
     want = np.array([float.fromhex(x) for x in g["sample_loads"]])
     assert_loads_close(load[np.asarray(g["sample_ids"])], want)
@@ -246,6 +265,39 @@ def test_c5_full_against_stored_oracle_values(a2a, oracle):
     b, st = topo.schedule_bound(topo_load_tensor(load), dtot, flags)
     assert st == 0 and b.argmax_arc == g["argmax_arc"]
     assert b.max_load * b.n_links / dtot == pytest.approx(g["ratio_links"], rel=1e-9)
+
+
+def test_c5_full_distance_matrix_bit_exact(a2a, oracle):
+    """a2a_distances over all 65 536 sources in one call (the configuration the benchmark times): the whole
+    int32 matrix and the per-source sums against the oracle, 2048 rows at a time."""
+    import torch
+    rp, col = gen.named_config("C5")
+    topo = a2a.Topology(rp, col)
+    N = topo.N
+    print("case C5 full distance matrix", flush=True)
+    ws = topo.alloc_workspace(N, a2a.WS_DISTANCES)
+    dist = torch.full((N, N), -9, dtype=torch.int32, device="cuda")
+    dsum = torch.full((N,), -1, dtype=torch.int64, device="cuda")
+    unr = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    topo.distances(0, N, dist=dist, dist_sum=dsum, unreachable=unr, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(unr.item()) == 0
+    got_sum = dsum.cpu().numpy()
+    chunk = 2048
+    for s0 in range(0, N, chunk):
+        o = oracle.run(rp, col, s0, chunk, threads=16, want_dist=True, want_load=False)
+        assert np.array_equal(dist[s0:s0 + chunk].cpu().numpy(), o.dist), s0
+        assert np.array_equal(got_sum[s0:s0 + chunk], o.dist_sum), s0
+        if s0 % (8 * chunk) == 0:
+            print(f"  rows {s0}..{s0 + chunk - 1} ok", flush=True)
+    del dist, ws
+    # path counts on 4096 sources spread over the range (the with-sigma code path), 512 at a time
+    for s0 in range(100, N, N // 8):
+        o = oracle.run(rp, col, s0, 512, threads=16, want_dist=True, want_sigma=True, want_load=False)
+        d2, sg, ds2, u2, f2 = run_distances(topo, s0, 512)
+        assert np.array_equal(d2, o.dist) and np.array_equal(ds2, o.dist_sum)
+        assert_sigma_equal(sg, o.sigma)
+        assert u2 == 0 and f2 == 0
     topo.close()
 
 
