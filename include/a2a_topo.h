@@ -126,6 +126,23 @@ int a2a_link_loads(const a2a_topo* topo, int32_t src_begin, int32_t src_count, d
                    size_t workspace_bytes, void* hip_stream);
 
 /*
+ * a2a_link_loads for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture set-up, tight serving loops, harnesses that forbid hipMalloc.  The workspace is
+ * a fixed array of A2A_STATIC_WORKSPACE_BYTES inside the library (one per GPU, held until the
+ * process ends; its address is looked up once, in a2a_topo_create); the call itself allocates
+ * nothing on the device and frees nothing.  Same arguments, results and reproducibility as
+ * a2a_link_loads with a workspace of that size (the batches advance in as many groups as the
+ * array holds).  A2A_ERR_WORKSPACE_TOO_SMALL, before anything is enqueued, if the array cannot hold
+ * one batch of this topology (a2a_workspace_bytes(topo, src_count, A2A_WS_LOADS | A2A_WS_MINIMAL)
+ * tells: about 0.9 KB per node and BFS level).  All calls on one GPU share the array, whatever
+ * the handle or stream: it keeps the previous call's contents (everything read is written first),
+ * and two such calls that overlap in time on one GPU race; serialise them.
+ */
+#define A2A_STATIC_WORKSPACE_BYTES (32u << 20)
+int a2a_link_loads_static(const a2a_topo* topo, int32_t src_begin, int32_t src_count, double* load,
+                          int64_t* dist_sum_total, int64_t* flags, void* hip_stream);
+
+/*
  * The same for commodities of unequal demand.  The paper's commodities all have the same
  * demand (Sec. 3.1.1); here the pair (s,t) carries demand(s,t), split equally over its
  * shortest paths as before (Sec. 5.2):

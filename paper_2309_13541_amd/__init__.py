@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     load_library,
     status_string,
     EXPORTED_SYMBOLS,
+    STATIC_WORKSPACE_BYTES,
     WS_DISTANCES, WS_SIGMA, WS_LOADS, WS_MINIMAL,
     FLAG_SIGMA_INEXACT, FLAG_UNREACHABLE,
     OK, ERR_INVALID_ARG, ERR_SELF_LOOP, ERR_WORKSPACE_TOO_SMALL, ERR_HIP, ERR_NOT_IMPLEMENTED,

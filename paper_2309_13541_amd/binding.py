@@ -39,7 +39,9 @@ EXPORTED_SYMBOLS = (
     "a2a_topo_create", "a2a_topo_destroy", "a2a_topo_info", "a2a_workspace_bytes",
     "a2a_distances", "a2a_link_loads", "a2a_link_loads_demand", "a2a_schedule_bound", "a2a_status_string",
     "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound", "a2a_schedule_bound_cap",
+    "a2a_link_loads_static",
 )
+STATIC_WORKSPACE_BYTES = 32 << 20
 
 PROF_KERNELS = ("init", "bfs", "offsets", "fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few", "bwd_spread",
                 "reduce", "extract")
@@ -155,6 +157,8 @@ def load_library():
     lib.a2a_distances.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.a2a_link_loads.restype = ctypes.c_int
     lib.a2a_link_loads.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.a2a_link_loads_static.restype = ctypes.c_int
+    lib.a2a_link_loads_static.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     lib.a2a_link_loads_demand.restype = ctypes.c_int
     lib.a2a_link_loads_demand.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.a2a_schedule_bound_cap.restype = ctypes.c_int
@@ -250,6 +254,13 @@ class Topology:
             self._h, src_begin, src_count, _ptr(load), _ptr(dist_sum_total), _ptr(flags),
             _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream)),
             "a2a_link_loads")
+
+    def link_loads_static(self, src_begin: int, src_count: int, *, load, dist_sum_total=None, flags=None,
+                          stream=None) -> int:
+        """a2a_link_loads on the library's fixed workspace array (no device allocation in the call)."""
+        return _check(load_library().a2a_link_loads_static(
+            self._h, src_begin, src_count, _ptr(load), _ptr(dist_sum_total), _ptr(flags), _stream(stream)),
+            "a2a_link_loads_static")
 
     def link_loads_demand(self, src_begin: int, src_count: int, *, demand, load, weighted_dist=None,
                           dist_sum_total=None, flags=None, workspace, stream=None) -> int:

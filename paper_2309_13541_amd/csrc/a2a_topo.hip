@@ -22,6 +22,11 @@
 
 using namespace a2a_dev;
 
+// Workspace of a2a_link_loads_static.  One copy per GPU, held until the process ends; in host
+// code this name only stands for the symbol: its address on a device is taken once, in
+// a2a_topo_create with that device current, and kept in the handle.
+static __device__ __align__(256) unsigned char scratch[A2A_STATIC_WORKSPACE_BYTES];
+
 struct a2a_topo {
   int32_t N = 0;
   int64_t E = 0;
@@ -34,6 +39,7 @@ struct a2a_topo {
   int32_t* d_in_col = nullptr;
   int64_t* h_pinned = nullptr;  // 16 x int64 pinned host words for read-backs
   int64_t* d_small = nullptr;   // 16 x int64 device words (schedule_bound result, profile counters)
+  void* d_scratch = nullptr;    // device address of `scratch` on the handle's GPU
   // optional per-kernel timing (a2a_profile_enable); events are created per launch while it is on
   struct ProfRec {
     int cls, level;
@@ -496,6 +502,7 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
             hipMalloc((void**)&t->d_in_col, cb) == hipSuccess &&
             hipMalloc((void**)&t->d_small, 16 * sizeof(int64_t)) == hipSuccess &&
             hipHostMalloc((void**)&t->h_pinned, 16 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipGetSymbolAddress(&t->d_scratch, HIP_SYMBOL(scratch)) == hipSuccess && t->d_scratch != nullptr;
   ok = ok && hipMemset(t->d_small, 0, 16 * sizeof(int64_t)) == hipSuccess &&
        hipMemcpy(t->d_out_ptr, row_ptr, pb, hipMemcpyHostToDevice) == hipSuccess &&
        hipMemcpy(t->d_in_ptr, in_ptr.data(), pb, hipMemcpyHostToDevice) == hipSuccess;
@@ -684,6 +691,18 @@ int a2a_link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, doub
                    void* hip_stream) {
   return link_loads(t, src_begin, src_count, nullptr, load, nullptr, dist_sum_total, flags, workspace,
                     workspace_bytes, hip_stream);
+}
+
+int a2a_link_loads_static(const a2a_topo* t, int32_t src_begin, int32_t src_count, double* load,
+                          int64_t* dist_sum_total, int64_t* flags, void* hip_stream) {
+  if (!t) return A2A_ERR_INVALID_ARG;
+  if (src_count > 0 && src_count <= t->N) {
+    // refuse before anything is enqueued: the array must hold at least one batch of this topology
+    const Layout L = make_layout(t, src_count, A2A_WS_LOADS, A2A_STATIC_WORKSPACE_BYTES, false, false);
+    if (L.G < 1) return A2A_ERR_WORKSPACE_TOO_SMALL;
+  }
+  return link_loads(t, src_begin, src_count, nullptr, load, nullptr, dist_sum_total, flags, t->d_scratch,
+                    A2A_STATIC_WORKSPACE_BYTES, hip_stream);
 }
 
 int a2a_link_loads_demand(const a2a_topo* t, int32_t src_begin, int32_t src_count, const double* demand,
