@@ -18,10 +18,17 @@
  *     buffer and the stream; the library owns only the opaque handle (a device copy of the
  *     out- and in-neighbour CSR, a few KB of pinned host memory).
  *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
- *     default stream).  a2a_distances and a2a_link_loads wait on that stream once per eight
- *     BFS levels and once more per batch group (the number of levels and how full they are
- *     is data dependent and decides what is launched next) and return with the remaining
- *     work enqueued; a2a_schedule_bound waits for its result.
+ *     default stream).  a2a_distances, a2a_link_loads, a2a_link_loads_demand and
+ *     a2a_link_loads_static only enqueue kernels of this library: they never wait for the device,
+ *     copy nothing to the host and allocate nothing, so they return while earlier work on the
+ *     stream may still be running, and a stream under HIP graph capture records them (the launch
+ *     sequence depends only on the handle, the source range and the workspace size; what depends
+ *     on the data is decided inside the kernels).  Exception: while a2a_profile_enable is on they
+ *     wait, to read counters back.  a2a_schedule_bound / _cap wait for their result; a2a_topo_create
+ *     runs a breadth-first search from every node on the default stream and waits for it.
+ *   - A handle may be used from several threads and streams at once, each call with its own
+ *     workspace and outputs (up to 64 a2a_schedule_bound / _cap calls in flight per handle);
+ *     a2a_profile_enable / _read are not thread safe.
  *   - Every function returns an a2a_status (0 = A2A_OK, negative = error); nothing throws,
  *     aborts or prints.  On error the outputs are unspecified.
  *   - Sources are processed in batches of 64 (one bit of a 64-bit mask per source); several
@@ -51,7 +58,7 @@ typedef enum a2a_status {
   A2A_ERR_NOT_IMPLEMENTED = -5,     /* N above 4 194 304 nodes (32-bit offsets into a batch's arrays) */
   A2A_ERR_DISCONNECTED = -6,        /* some ordered pair has no path: all-to-all infeasible */
   A2A_ERR_NO_MEMORY = -7,           /* host allocation failed */
-  A2A_ERR_LEVEL_OVERFLOW = -8       /* BFS went deeper than the level bound of the handle */
+  A2A_ERR_LEVEL_OVERFLOW = -8       /* not returned any more (the handle knows the deepest BFS level) */
 } a2a_status;
 
 /* flags of a2a_workspace_bytes */
@@ -73,8 +80,10 @@ typedef enum a2a_status {
  *   out      receives the handle; release with a2a_topo_destroy
  * Validation happens before the first HIP call, so malformed input is reported as
  * A2A_ERR_INVALID_ARG / A2A_ERR_SELF_LOOP even on a machine without a GPU.
- * The handle also records a level bound: an upper bound on the largest finite D(s,t)
- * (eccentricities of node 0 in both directions if G is strongly connected, else N-1).
+ * The handle also records the largest finite D(s,t) over all ordered pairs ("level bound"; the
+ * diameter if G is strongly connected), found by a breadth-first search from every node on the
+ * device (about 1 GiB of temporary device memory at most, freed before returning).  It fixes the
+ * number of BFS levels, hence kernel launches and workspace level slots, of every later call.
  */
 int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a2a_topo** out);
 
@@ -114,9 +123,10 @@ int a2a_distances(const a2a_topo* topo, int32_t src_begin, int32_t src_count, in
  * src_begin .. src_begin+src_count-1 (0, N = the full all-to-all):
  *   load[a] = sum_s sum_{t != s} (# shortest s->t paths through link a) / sigma(s,t).
  * Computed per source batch by a forward path-count pass and a backward dependency pass over
- * the shortest-path DAG; batch results are added in ascending batch order, so the result is
- * bitwise reproducible from run to run for a given workspace size (the size decides which
- * batches advance together, and with it the summation order inside a batch).
+ * the shortest-path DAG; batch results are added in ascending batch order and every sum is taken
+ * in a fixed order, so the result is bitwise reproducible from run to run and does not depend on
+ * the workspace size (the size decides which batches advance together, never the order of a sum:
+ * every batch picks its kernels' lane layout from its own level sizes).
  *   load            device, double[E], overwritten
  *   dist_sum_total  device, int64[1]: sum over these sources of sum_t D(s,t).  May be NULL.
  *   flags           device, int64[1]: A2A_FLAG_* bits.  May be NULL.
@@ -131,8 +141,7 @@ int a2a_link_loads(const a2a_topo* topo, int32_t src_begin, int32_t src_count, d
  * a fixed array of A2A_STATIC_WORKSPACE_BYTES inside the library (one per GPU, held until the
  * process ends; its address is looked up once, in a2a_topo_create); the call itself allocates
  * nothing on the device and frees nothing.  Same arguments, results and reproducibility as
- * a2a_link_loads with a workspace of that size (the batches advance in as many groups as the
- * array holds).  A2A_ERR_WORKSPACE_TOO_SMALL, before anything is enqueued, if the array cannot hold
+ * a2a_link_loads (the batches advance in as many groups as the array holds).  A2A_ERR_WORKSPACE_TOO_SMALL, before anything is enqueued, if the array cannot hold
  * one batch of this topology (a2a_workspace_bytes(topo, src_count, A2A_WS_LOADS | A2A_WS_MINIMAL)
  * tells: about 0.9 KB per node and BFS level).  All calls on one GPU share the array, whatever
  * the handle or stream: it keeps the previous call's contents (everything read is written first),
@@ -198,7 +207,7 @@ int a2a_schedule_bound(const a2a_topo* topo, const double* load, int64_t sum_dis
 
 /*
  * The same for a network G = (V, E, cap) with link capacities, the general form of the problem
- * (Sec. 3.1.1; "a multiplier ... if link bandwidth is not uniform", Sec. 3.1.1 time-stepped LP):
+ * (Sec. 3.1.1, and the remark on non-uniform link bandwidth in the time-stepped LP there):
  * the flows of a routing fit when every link's load times the common rate stays within its
  * capacity, so the all-to-all time of the EwSP routing is the largest utilisation load[a] / cap[a].
  * cap[a] is the bandwidth of link a in units of b (cap = 1 everywhere gives a2a_schedule_bound).
@@ -259,7 +268,10 @@ int a2a_tree_lower_bound(int32_t N, int32_t d, double m_bytes, double b_bytes_pe
  *   2  as 1, and the forward pass also counts the (source, link) pairs that lie on shortest
  *      paths (one atomic per wavefront: slows the forward kernels down, use on untimed runs).
  * a2a_profile_read waits for the device and sums the event times per kernel class; index
- * A2A_PROF_* into ms[] / launches[].  Not thread safe.
+ * A2A_K_* into ms[] / launches[].  One launch serves a level of all batches of a group and every
+ * batch picks its own lane layout inside it; a launch is filed under the layout that the group's
+ * average level size stands for (FWD_ROWS / FWD_FEW / FWD_SPREAD, BWD_...).  While a mode other
+ * than 0 is on, the compute calls wait for the device to read counters back.  Not thread safe.
  */
 typedef enum a2a_prof_kernel {
   A2A_K_INIT = 0,  /* level 0 set-up */
@@ -290,6 +302,12 @@ typedef struct a2a_profile {
                                                   counts of level l-1 in single precision (the library
                                                   keeps them so while (largest in-degree)^level < 2^24:
                                                   exact, half the bytes) */
+  uint64_t fwd_flavours;                       /* lane layouts the batches' forward levels picked: bit
+                                                  3 * layout + p, layout 0 rows, 1 spread, 2 (node, source),
+                                                  3 (node, link); p = 0 float -> float, 1 float -> double,
+                                                  2 double -> double path counts */
+  uint64_t bwd_flavours;                       /* the same backward: bit 2 * layout + p, p = 0 float,
+                                                  1 double path counts on the level */
 } a2a_profile;
 int a2a_profile_enable(a2a_topo* topo, int mode);
 int a2a_profile_read(a2a_topo* topo, a2a_profile* out);

@@ -101,11 +101,13 @@ class Profile(ctypes.Structure):
                 ("pairs_level", ctypes.c_int64 * PROF_MAX_LEVELS),
                 ("dag_level", ctypes.c_int64 * PROF_MAX_LEVELS),
                 ("dag_links", ctypes.c_int64), ("calls", ctypes.c_int64),
-                ("depth", ctypes.c_int32), ("groups", ctypes.c_int32), ("narrow_levels", ctypes.c_uint64)]
+                ("depth", ctypes.c_int32), ("groups", ctypes.c_int32), ("narrow_levels", ctypes.c_uint64),
+                ("fwd_flavours", ctypes.c_uint64), ("bwd_flavours", ctypes.c_uint64)]
 
     def as_dict(self) -> dict:
         d = {"dag_links": self.dag_links, "calls": self.calls, "depth": self.depth,
-             "groups": self.groups, "narrow_levels": self.narrow_levels, "pairs_level": list(self.pairs_level),
+             "groups": self.groups, "narrow_levels": self.narrow_levels, "fwd_flavours": self.fwd_flavours,
+             "bwd_flavours": self.bwd_flavours, "pairs_level": list(self.pairs_level),
              "dag_level": list(self.dag_level)}
         for i, n in enumerate(PROF_KERNELS):
             d[n] = {"ms": self.ms[i], "launches": self.launches[i], "ms_level": list(self.ms_level[i])}

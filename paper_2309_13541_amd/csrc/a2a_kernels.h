@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(kBfsBlock) k_init_group(GroupView gv) {
 // Thread (node, k): the kSub lanes of a node read the same in-link list and adjacent masks.
 __global__ void __launch_bounds__(kBfsBlock)
 k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
-            int level, int* __restrict__ level_new) {
+            int level) {
   int sb, nblk;
   if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
   const int t = (int)threadIdx.x;
@@ -385,10 +385,7 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   if (t < kSub) {
     const int tot = s_cnt[t];
     gv.bsum[((size_t)g * gv.Lcap + level) * gv.nb64 + nblk] = tot;
-    if (tot > 0) {
-      atomicAdd((unsigned long long*)&gv.ltot[(size_t)g * gv.Lcap + level], (unsigned long long)tot);
-      level_new[level] = 1;
-    }
+    if (tot > 0) atomicAdd((unsigned long long*)&gv.ltot[(size_t)g * gv.Lcap + level], (unsigned long long)tot);
   }
 }
 
@@ -544,14 +541,10 @@ __device__ __forceinline__ bool fwd_finish(TOut* __restrict__ out, double* __res
 
 // TIn / TOut: precision in which the level before / this level keeps sigma (the host's choice).
 template <bool kCountDag, typename TIn, typename TOut>
-__global__ void __launch_bounds__(kBlock)
-k_fwd_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv,
-            int level, bool init_coef, long long* __restrict__ misc) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+__device__ __forceinline__ void
+fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv,
+         int level, bool init_coef, long long* __restrict__ misc, int g, int v0) {
   const int lane = lane_id();
-  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (v0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
@@ -697,14 +690,10 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
 
 // TS: precision in which this level keeps sigma.  kDemand: commodities of unequal demand.
 template <typename TS, bool kDemand>
-__global__ void __launch_bounds__(kBlock)
-k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv,
-            int level) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+__device__ __forceinline__ void
+bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv,
+         int level, int g, int u0, double* __restrict__ sum8_buf) {
   const int lane = lane_id();
-  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
   const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
@@ -712,8 +701,6 @@ k_bwd_level(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
   double wd = 0.0;  // this lane's source: demands met
-  __shared__ double s_sum8[kWavesPerBlock][kSum8Doubles];
-  double* sum8_buf = s_sum8[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -1010,14 +997,10 @@ __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* _
 }
 
 template <bool kCountDag, bool kSlots, typename TIn, typename TOut>
-__global__ void __launch_bounds__(kBlock)
-k_fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
-          bool init_coef, long long* __restrict__ misc) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+__device__ __forceinline__ void
+fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
+        bool init_coef, long long* __restrict__ misc, int g, int v0) {
   const int lane = lane_id();
-  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (v0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
@@ -1109,21 +1092,15 @@ __device__ __forceinline__ void spread_link(const T* __restrict__ rows, const Ti
 }
 
 template <bool kCountDag, typename TIn, typename TOut>
-__global__ void __launch_bounds__(kBlock)
-k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
-             bool init_coef, long long* __restrict__ misc) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+__device__ __forceinline__ void
+fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
+           bool init_coef, long long* __restrict__ misc, int g, int v0, double (*__restrict__ acc)[kWave]) {
   const int lane = lane_id();
-  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (v0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
   TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  __shared__ double s_acc[kWavesPerBlock][8][kWave];  // [node of the tile][source]
-  double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -1184,17 +1161,53 @@ k_fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_
 
 // --- backward level whose successors' rows are short: the mirror image ----------------------
 //
-// A level with many sources per node whose successors have few: the node's sigma and 1/sigma go
-// to LDS (a lane per source), then lane 8i+j reads the coef row of link j of node i from end to
-// end, adds every entry whose source the node has on this level to the node's accumulator for
-// that source and, times the node's sigma, to the link's load (lane-local, in row order); then
-// the accumulators go to the node's coef row, a lane per source.  The accumulators are private to
-// the wave and start at zero: one or two contributions add up to the same bits in either order;
-// three or more (rare: a source with three successors of one node) arrive in program order and,
-// inside one instruction, in the order in which the LDS serves the lanes that collide.
+// A level with many sources per node whose successors have few: the node's sigma goes to LDS (a
+// lane per source), then lane 8i+j reads the coef row of link j of node i from end to end, adds
+// every entry whose source the node has on this level to the node's accumulator for that source
+// and, times the node's sigma, to the link's load (lane-local, in row order); then the
+// accumulators go to the node's coef row, a lane per source.  The order of every sum is fixed.
+// The accumulators are private to the wave and start at zero, so a source that at most two of the
+// node's eight links carry gets the same bits whichever of the two lanes is served first (the
+// common case: atomic adds, all links at once).  Sources carried by three or more links of the
+// tile, and everything in the further tiles of a node with more than eight links, take the ordered
+// path instead: source by source, the eight lanes' values added in a fixed tree, one lane adding
+// the result to the accumulator.
 
-__device__ __forceinline__ double spread_link_bwd(const double* __restrict__ rows, const Tile& tl, uint64_t mu,
-                                                  double* __restrict__ acc, const double* __restrict__ sig) {
+template <int kMask>
+__device__ __forceinline__ uint64_t xor_lanes_u64(uint64_t x) {
+  return (uint64_t)__double_as_longlong(xor_lanes<kMask>(__longlong_as_double((long long)x)));
+}
+
+// Bits set in at least three of the eight masks held by the lanes 8i .. 8i+7 (the same result in
+// all eight): a carry-save count over the three exchange steps.
+__device__ __forceinline__ uint64_t three_or_more8(uint64_t m) {
+  const uint64_t b = xor_lanes_u64<1>(m);
+  uint64_t ones = m ^ b, twos = m & b;  // pair: count = ones + 2 twos
+  const uint64_t o2 = xor_lanes_u64<2>(ones), t2 = xor_lanes_u64<2>(twos);
+  const uint64_t c1 = ones & o2;
+  ones ^= o2;
+  const uint64_t fours = (twos & t2) | (twos & c1) | (t2 & c1);
+  twos = twos ^ t2 ^ c1;  // four lanes: count = ones + 2 twos + 4 fours
+  const uint64_t o3 = xor_lanes_u64<4>(ones), t3 = xor_lanes_u64<4>(twos), f3 = xor_lanes_u64<4>(fours);
+  const uint64_t c2 = ones & o3;
+  ones ^= o3;
+  const uint64_t c4 = (twos & t3) | (twos & c2) | (t3 & c2);
+  twos = twos ^ t3 ^ c2;
+  return fours | f3 | c4 | (twos & ones);
+}
+
+__device__ __forceinline__ uint64_t or8(uint64_t m) {
+  m |= xor_lanes_u64<1>(m);
+  m |= xor_lanes_u64<2>(m);
+  m |= xor_lanes_u64<4>(m);
+  return m;
+}
+
+// Fast path: the entries of this lane's link whose source is in `take` (sources of the node that at
+// most two links of the tile carry).  Returns tot + this lane's share of the link load.
+template <typename TS>
+__device__ __forceinline__ double spread_link_bwd(const double* __restrict__ rows, const Tile& tl, uint64_t take,
+                                                  double* __restrict__ acc, const TS* __restrict__ sig) {
   // entry by entry: with one or two entries per row, pairs (as in spread_link) only fetch more
   uint64_t rest = tl.mask;
   uint32_t e = tl.off;
@@ -1212,9 +1225,9 @@ __device__ __forceinline__ double spread_link_bwd(const double* __restrict__ row
       if (rest != 0) {
         const int s = __builtin_ctzll(rest);
         rest &= rest - 1;
-        if ((mu >> s) & 1ull) {
+        if ((take >> s) & 1ull) {
           unsafeAtomicAdd(&acc[s], x[k]);
-          tot = __builtin_fma(sig[s], x[k], tot);
+          tot = __builtin_fma((double)sig[s], x[k], tot);
         }
       }
     }
@@ -1223,14 +1236,34 @@ __device__ __forceinline__ double spread_link_bwd(const double* __restrict__ row
   return tot;
 }
 
+// Ordered path: the sources in `set` (the same in the eight lanes of a node), lowest first.  Each
+// lane fetches its link's entry for the source (0 if the link does not carry it), the eight
+// values are added in a fixed tree, and the node's first lane adds the sum to the accumulator.
+template <typename TS>
+__device__ __forceinline__ double spread_ordered_bwd(const double* __restrict__ rows, const Tile& tl, uint64_t set,
+                                                     double* __restrict__ acc, const TS* __restrict__ sig,
+                                                     double tot, int lane) {
+  uint64_t todo = or8(tl.mask & set);
+  while (__ballot(todo != 0) != 0) {
+    const bool live = todo != 0;
+    const int s = live ? __builtin_ctzll(todo) : 0;
+    todo &= todo - 1;
+    double x = 0.0;
+    if (live && ((tl.mask >> s) & 1ull)) x = entry(rows, tl.off + below(tl.mask, s));
+    tot = __builtin_fma((double)sig[s], x, tot);
+    double y = x + xor_lanes<1>(x);
+    y += xor_lanes<2>(y);
+    y += xor_lanes<4>(y);
+    if (live && (lane & 7) == 0) acc[s] += y;
+  }
+  return tot;
+}
+
 template <typename TS, bool kDemand>
-__global__ void __launch_bounds__(kBlock)
-k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+__device__ __forceinline__ void
+bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
+           int g, int u0, double (*__restrict__ acc)[kWave], TS (*__restrict__ sig)[kWave]) {
   const int lane = lane_id();
-  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
   const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
@@ -1238,9 +1271,6 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
   double wd = 0.0;
-  __shared__ double s_acc[kWavesPerBlock][8][kWave], s_sig[kWavesPerBlock][8][kWave];  // [node of the tile][source]
-  double(*acc)[kWave] = s_acc[threadIdx.x / kWave];
-  double(*sig)[kWave] = s_sig[threadIdx.x / kWave];
   const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
@@ -1274,20 +1304,23 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         sg[i] = (double)hold(sg_own[i]);
-        sig[i][lane] = sg[i];
+        sig[i][lane] = (TS)sg[i];  // exact: it came from a TS
         acc[i][lane] = 0.0;
       }
       __builtin_amdgcn_wave_barrier();
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
-      const double tot = spread_link_bwd(cf, tile, mu, acc[lane >> 3], sig[lane >> 3]);
+      const uint64_t many = three_or_more8(tile.mask & mu);
+      double tot = spread_link_bwd(cf, tile, mu & ~many, acc[lane >> 3], sig[lane >> 3]);
+      __builtin_amdgcn_wave_barrier();
+      tot = spread_ordered_bwd(cf, tile, many, acc[lane >> 3], sig[lane >> 3], tot, lane);
       if (q >= 0 && (tile.mask & mu) != 0) unsafeAtomicAdd(&pt[q], tot);
       // nodes with more than eight out-links: further tiles into the same accumulators
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         int qe;
         const Tile extra = tile_request_idx(next, tile_request_col(out_col, lr, c, base, lane, qe));
-        const double te = spread_link_bwd(cf, extra, mu, acc[lane >> 3], sig[lane >> 3]);
+        const double te = spread_ordered_bwd(cf, extra, mu, acc[lane >> 3], sig[lane >> 3], 0.0, lane);
         if (qe >= 0 && (extra.mask & mu) != 0) unsafeAtomicAdd(&pt[qe], te);
       }
       __builtin_amdgcn_wave_barrier();
@@ -1310,13 +1343,10 @@ k_bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ ou
 }
 
 template <bool kSlots, typename TS, bool kDemand>
-__global__ void __launch_bounds__(kBlock)
-k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+__device__ __forceinline__ void
+bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
+        int g, int u0) {
   const int lane = lane_id();
-  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (u0 >= gv.N) return;
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
   const TS* __restrict__ dat = sigma_rows<TS>(gv, g);
@@ -1365,6 +1395,103 @@ k_bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_c
     q_next = q_nn;
   }
   if (kDemand) add_weighted_dist(gv, g, u0, level, wd);
+}
+
+// --- one launch per level and pass; every batch picks its own lane layout --------------------
+//
+// How full a level is differs from batch to batch (and from topology to topology), and it decides
+// which of the lane layouts above is the cheap one.  The choice is made here, per batch, from the
+// batch's own pair counts (ltot, complete after the BFS): it does not depend on which batches
+// happen to advance together, so neither do the sums' orders nor the results' bits, and the host
+// needs no read-back to pick a kernel.  sources per node = pairs / N:
+//   >= kRowsLanes                       lane = source, one wave per node          (rows)
+//   ... and the level the pass reads from (the one before, forward; the one after, backward)
+//       below kRowsLanes                lane = (node, link), whole rows           (spread)
+//   kSlotLanes .. kRowsLanes            lane = (node, source)                     (few, slots)
+//   below kSlotLanes                    lane = (node, link), source by source     (few)
+constexpr long long kRowsLanes = 8;
+constexpr long long kSlotLanes = 2;
+
+enum Flavour { kFlavRows = 0, kFlavSpread = 1, kFlavSlots = 2, kFlavFew = 3 };
+
+// Pairs on the level, on the one before and on the one after, for batch g.
+struct LevelFill {
+  long long before, here, after;
+};
+__device__ __forceinline__ LevelFill level_fill(const GroupView& gv, int g, int level) {
+  const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
+  LevelFill f;
+  f.before = level > 0 ? lt[level - 1] : 0;
+  f.here = lt[level];
+  f.after = level + 1 < gv.Lcap ? lt[level + 1] : 0;
+  return f;
+}
+__host__ __device__ __forceinline__ int pick_flavour(long long here, long long other, long long N) {
+  if (here >= kRowsLanes * N) return (other > 0 && other < kRowsLanes * N) ? kFlavSpread : kFlavRows;
+  return here >= kSlotLanes * N ? kFlavSlots : kFlavFew;
+}
+
+// sigma of one level (1 .. deepest) for every batch of the group.  The batch's deepest level also
+// gets coef = 1 / sigma (unit demands: there is nothing to add to it).
+template <bool kCountDag, typename TIn, typename TOut>
+__global__ void __launch_bounds__(kBlock)
+k_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
+      long long* __restrict__ misc) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const LevelFill f = level_fill(gv, g, level);
+  if (f.here == 0) return;
+  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (v0 >= gv.N) return;
+  __shared__ double s_acc[kWavesPerBlock][8][kWave];  // spread: [node of the tile][source]
+  const bool init_coef = gv.coef != nullptr && gv.dem == nullptr && f.after == 0;
+  switch (pick_flavour(f.here, f.before, gv.N)) {
+    case kFlavRows:
+      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0);
+      break;
+    case kFlavSpread:
+      fwd_spread<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, s_acc[threadIdx.x / kWave]);
+      break;
+    case kFlavSlots:
+      fwd_few<kCountDag, true, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0);
+      break;
+    default:
+      fwd_few<kCountDag, false, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0);
+      break;
+  }
+}
+
+// coef and link loads of one level for every batch of the group.  With unit demands a batch's
+// deepest level is skipped: the forward pass left its coef.
+template <typename TS, bool kDemand>
+__global__ void __launch_bounds__(kBlock)
+k_bwd(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  const LevelFill f = level_fill(gv, g, level);
+  if (f.here == 0 || (!kDemand && f.after == 0)) return;
+  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  if (u0 >= gv.N) return;
+  // rows: the eight 64-lane sums of a node; spread: accumulators and sigma, [node of the tile][source]
+  constexpr int kSpreadDoubles = 8 * kWave + 8 * kWave * (int)sizeof(TS) / 8;
+  constexpr int kBufDoubles = kSpreadDoubles > kSum8Doubles ? kSpreadDoubles : kSum8Doubles;
+  __shared__ double s_buf[kWavesPerBlock][kBufDoubles];
+  double* buf = s_buf[threadIdx.x / kWave];
+  switch (pick_flavour(f.here, f.after, gv.N)) {
+    case kFlavRows:
+      bwd_rows<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, buf);
+      break;
+    case kFlavSpread:
+      bwd_spread<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, reinterpret_cast<double(*)[kWave]>(buf),
+                              reinterpret_cast<TS(*)[kWave]>(buf + 8 * kWave));
+      break;
+    case kFlavSlots:
+      bwd_few<true, TS, kDemand>(out_ptr, out_col, gv, level, g, u0);
+      break;
+    default:
+      bwd_few<false, TS, kDemand>(out_ptr, out_col, gv, level, g, u0);
+      break;
+  }
 }
 
 // load[a] = (first group ? 0 : load[a]) + part[0][a] + part[1][a] + ... in that order.
@@ -1548,21 +1675,80 @@ k_fold_counters(GroupView gv, int depth, long long* __restrict__ misc) {
   }
 }
 
-// *out += wpart[0] + wpart[1] + ... : thread t adds the elements t, t + kBlock, ... in that order,
-// then the threads' sums are added in a fixed tree.
+// Demand x distance of a call: each batch's blocks are added up in a fixed tree (one workgroup per
+// batch; the sum lands in the batch's first slot), then the batches are added to *out one after the
+// other in ascending order, so the bits do not depend on which batches share a group.
 __global__ void __launch_bounds__(kBlock)
-k_fold_weighted(const double* __restrict__ wpart, long long n, double* __restrict__ out) {
+k_fold_weighted_batch(double* __restrict__ wpart, int nb64) {
   __shared__ double s_r[kBlock];
   const int t = (int)threadIdx.x;
+  double* __restrict__ w = wpart + (size_t)blockIdx.x * nb64;
   double x = 0.0;
-  for (long long i = t; i < n; i += kBlock) x += wpart[i];
+  for (int i = t; i < nb64; i += kBlock) x += w[i];
   s_r[t] = x;
   __syncthreads();
   for (int o = kBlock / 2; o > 0; o >>= 1) {
     if (t < o) s_r[t] += s_r[t + o];
     __syncthreads();
   }
-  if (t == 0) out[0] += s_r[0];
+  if (t == 0) w[0] = s_r[0];
+}
+__global__ void k_fold_weighted(const double* __restrict__ wpart, int G, int nb64, double* __restrict__ out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double run = out[0];
+    for (int g = 0; g < G; ++g) run += wpart[(size_t)g * nb64];
+    out[0] = run;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// level probe (a2a_topo_create): how deep does the BFS go from any source
+// ---------------------------------------------------------------------------------------
+
+// The BFS of k_bfs_level with two mask arrays used in turn instead of one per level, and no
+// counting: a2a_topo_create runs it from every node once to learn the largest finite distance,
+// which sizes the level slots of every later call.  Arrays: [SB][Npad][kSub].
+__global__ void __launch_bounds__(kBfsBlock)
+k_probe_init(uint64_t* __restrict__ front, uint64_t* __restrict__ seen, int N, int Npad, int SB, int src0) {
+  int sb, nblk;
+  if (!map_block(SB, Npad / kBfsNodes, kXcd, sb, nblk)) return;
+  const int t = (int)threadIdx.x;
+  const int v = nblk * kBfsNodes + t / kSub, k = t % kSub;
+  const int s0 = src0 + (sb * kSub + k) * 64;
+  const int j = v - s0;
+  const uint64_t bit = (v < N && j >= 0 && j < 64) ? (1ull << j) : 0ull;
+  const size_t at = ((size_t)sb * Npad + v) * kSub + k;
+  front[at] = bit;
+  seen[at] = bit;
+}
+__global__ void __launch_bounds__(kBfsBlock)
+k_probe_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col,
+              const uint64_t* __restrict__ prev, uint64_t* __restrict__ next, uint64_t* __restrict__ seen, int N,
+              int Npad, int SB, int* __restrict__ reached) {
+  int sb, nblk;
+  if (!map_block(SB, Npad / kBfsNodes, kXcd, sb, nblk)) return;
+  const int t = (int)threadIdx.x;
+  const int v = nblk * kBfsNodes + t / kSub, k = t % kSub;
+  const size_t at = ((size_t)sb * Npad + v) * kSub + k;
+  const uint64_t* __restrict__ pv = prev + (size_t)sb * Npad * kSub + k;
+  uint64_t nw = 0;
+  if (v < N) {
+    const uint64_t sn = seen[at];
+    uint64_t acc = 0;
+    const int p1 = in_ptr[v + 1];
+    for (int p = in_ptr[v]; p < p1; p += 8) {
+      int u[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) u[j] = p + j < p1 ? in_col[p + j] : -1;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (u[j] >= 0) acc |= pv[(size_t)u[j] * kSub];
+    }
+    nw = acc & ~sn;
+    if (nw) seen[at] = sn | nw;
+  }
+  next[at] = nw;
+  if (__ballot(nw != 0) != 0 && lane_id() == 0) *reached = 1;
 }
 
 // Final outputs of a call: totals and flag bits (bit 0: sigma reached 2^53, bit 1: some pair

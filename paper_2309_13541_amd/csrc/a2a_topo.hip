@@ -4,13 +4,18 @@
 //
 // A "group" of G source batches (64 sources each) advances level by level together, one kernel
 // launch per level and pass, as many batches as the caller's workspace holds:
-//   bfs    all levels (one host read-back per level tells when the frontier is empty)
+//   bfs    levels 1 .. deepest (the handle knows the deepest level any source reaches)
 //   offs   row offsets of the level-compact value array
-//   fwd    levels 1..depth: sigma
-//   bwd    levels depth..0: coef and per-batch link loads
+//   fwd    levels 1 .. deepest: sigma
+//   bwd    levels deepest .. 0: coef and per-batch link loads
 //   sum    load += per-batch loads, in ascending batch order
+// Nothing in a2a_distances / a2a_link_loads waits for the device or reads anything back: the
+// launch sequence is fixed by the handle, and what depends on the data (which levels a batch
+// has, how full they are) is decided inside the kernels.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -32,13 +37,18 @@ struct a2a_topo {
   int64_t E = 0;
   int32_t dmax = 0;
   int32_t dmax_in = 0;  // largest in-degree
-  int32_t level_bound = 0;
+  int32_t level_bound = 0;  // largest finite D(s,t), found by the level probe at create
   int32_t* d_out_ptr = nullptr;
   int32_t* d_out_col = nullptr;
   int32_t* d_in_ptr = nullptr;
   int32_t* d_in_col = nullptr;
-  int64_t* h_pinned = nullptr;  // 16 x int64 pinned host words for read-backs
-  int64_t* d_small = nullptr;   // 16 x int64 device words (schedule_bound result, profile counters)
+  // Read-back slots of a2a_schedule_bound / _cap: kSlots x kSlotWords int64 on the device and in
+  // pinned host memory; every call takes the next slot, so calls on different streams or threads
+  // do not share one.
+  static constexpr unsigned kSlots = 64, kSlotWords = 8;
+  int64_t* h_pinned = nullptr;
+  int64_t* d_small = nullptr;
+  mutable std::atomic<unsigned> next_slot{0};
   void* d_scratch = nullptr;    // device address of `scratch` on the handle's GPU
   // optional per-kernel timing (a2a_profile_enable); events are created per launch while it is on
   struct ProfRec {
@@ -53,6 +63,7 @@ struct a2a_topo {
   mutable int32_t prof_depth = 0;
   mutable int32_t prof_groups = 0;
   mutable uint64_t prof_narrow = 0;
+  mutable uint64_t prof_fwd_flavours = 0, prof_bwd_flavours = 0;
 };
 
 namespace {
@@ -76,7 +87,6 @@ struct Layout {
   int SB = 0;    // super-batches of kSub batches (BFS arrays)
   bool values = false, loads = false;
   size_t Epad = 0;
-  size_t off_level_new = 0;  // int32 [Lcap]
   size_t off_misc = 0;       // int64 [8]: 0 sigma-inexact flag, 1 dist_sum, 2 reached pairs, 3 DAG links
   size_t off_ltot = 0;       // int64 [G][Lcap]
   size_t off_dag = 0;        // int64 [G][Lcap]
@@ -113,7 +123,6 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       off += align_up(bytes, 256);
       return at;
     };
-    const size_t o_level_new = take((size_t)L.Lcap * 4);
     const size_t o_misc = take(64);
     const size_t SB = (size_t)(G + kSub - 1) / kSub;
     const size_t o_ltot = take(SB * kSub * L.Lcap * 8);
@@ -128,7 +137,6 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     const size_t o_wpart = L.loads ? take((size_t)G * L.nb64 * 8) : 0;
     if (out) {
-      out->off_level_new = o_level_new;
       out->off_misc = o_misc;
       out->off_ltot = o_ltot;
       out->off_dag = o_dag;
@@ -211,37 +219,13 @@ inline unsigned grid_for(int G, int blocks_per_batch, int inflight = kXcd) {
   return (unsigned)((G + inflight - 1) / inflight * inflight * blocks_per_batch);
 }
 
-// Eccentricity of node 0 over the given CSR by queue BFS; -1 if some node is not reached.
-int host_ecc0(int32_t N, const int32_t* ptr, const int32_t* col) {
-  std::vector<int32_t> d((size_t)N, -1), q((size_t)N);
-  int head = 0, tail = 0, ecc = 0;
-  d[0] = 0;
-  q[tail++] = 0;
-  while (head < tail) {
-    const int u = q[head++];
-    for (int p = ptr[u]; p < ptr[u + 1]; ++p) {
-      const int w = col[p];
-      if (d[w] < 0) {
-        d[w] = d[u] + 1;
-        ecc = d[w];
-        q[tail++] = w;
-      }
-    }
-  }
-  return tail == N ? ecc : -1;
-}
-
-// Which kernel flavour a level gets, from the average number of sources per node on it:
-// below kFewLanes the lanes of a wave stand for (node, link) or (node, source) pairs of eight
-// nodes (k_fwd_few / k_bwd_few), from kSlotLanes on in the (node, source) layout; above, one wave
-// per node with a lane per source (k_fwd_level / k_bwd_level), unless the level the pass reads
-// from (the one before, forward; the one after, backward) is below kFewLanes: then a lane per
-// (node, link) reads whole rows (k_fwd_spread / k_bwd_spread).
-constexpr double kFewLanes = 8.0;
-constexpr double kSlotLanes = 2.0;
 // Largest topology: a batch's value array (N * 64 entries of 8 bytes) is addressed with 32-bit
 // byte offsets.
 constexpr int32_t kMaxNodes = 4 * 1024 * 1024;
+
+// Nominal lane layout of a level for the profile's kernel classes (the kernels pick per batch,
+// from the same rule applied to the batch's own counts).
+constexpr double kNominalRows = 8.0;
 
 struct Run {
   const a2a_topo* t;
@@ -251,13 +235,12 @@ struct Run {
   int src_begin, src_count;
   const double* demand = nullptr;  // [N][src_count] by target, or nullptr: every pair has demand 1
   int inflight = kXcd;  // batches in flight = XCDs: one batch's node blocks per XCD at a time
-  mutable std::vector<double> lanes_per_node;  // per level of the current group: pairs / (G*N)
+  mutable std::vector<double> lanes_per_node;  // profiling only: per level of the current group, pairs / (G*N)
   bool few(int level) const {
-    return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] < kFewLanes;
+    return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] > 0.0 &&
+           lanes_per_node[level] < kNominalRows;
   }
-  bool slots(int level) const { return lanes_per_node[level] >= kSlotLanes; }
-  // Many sources per node on this level, few on the other one the pass looks at.
-  bool fwd_spread(int level) const { return level > 0 && !few(level) && few(level - 1); }
+  bool rows(int level) const { return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] >= kNominalRows; }
   // Path counts on `level` are at most (largest in-degree)^level: while that is below 2^24 the level
   // keeps sigma in single precision (exact: whole numbers a float holds), which halves what the
   // forward pass writes and gathers and what the backward pass reads of it.  If a level is narrow,
@@ -268,8 +251,6 @@ struct Run {
     while (n < L.Lcap && narrow(n)) ++n;
     return n;
   }
-  bool bwd_spread(int level, int depth) const { return level < depth && !few(level) && few(level + 1); }
-  int* level_new() const { return (int*)(ws + L.off_level_new); }
   long long* misc() const { return (long long*)(ws + L.off_misc); }
   GroupView view(int batch0, int G) const {
     GroupView gv;
@@ -303,72 +284,65 @@ struct Run {
   }
 };
 
-// BFS of one group; *depth = deepest non-empty level.
-int run_bfs(const Run& r, const GroupView& gv, int* depth) {
+// BFS of one group: levels 1 .. top (the handle's deepest level, one more when the backward pass
+// will look at the empty level after a batch's last one).
+int run_bfs(const Run& r, const GroupView& gv, int top) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
-  HIP_TRY(zero_async(r.level_new(), (size_t)L.Lcap * 4, r.st));
   HIP_TRY(zero_async(gv.ltot, (size_t)gv.SB * kSub * L.Lcap * 8, r.st));
   {
     ProfScope ps(t, PROF_INIT, r.st);
     k_init_group<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv);
   }
-  // Levels are launched kLevelChunk at a time and the "frontier not empty" flags read back once per
-  // chunk: the depth is data dependent, and a host round trip per level costs more than the few
-  // empty levels a chunk may run past the last one.
-  constexpr int kLevelChunk = 8;
-  int d = 0;
-  int l = 1;
-  bool done = false;
-  while (!done && l < L.Lcap) {
-    const int first = l, last = std::min(l + kLevelChunk, L.Lcap);  // levels first .. last-1
-    for (; l < last; ++l) {
-      ProfScope ps(t, PROF_BFS, r.st, l);
-      k_bfs_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l,
-                                                                   r.level_new());
-    }
-    HIP_TRY(hipMemcpyAsync(t->h_pinned, r.level_new() + first, (size_t)(last - first) * 4, hipMemcpyDeviceToHost,
-                           r.st));
-    HIP_TRY(hipStreamSynchronize(r.st));
-    const int32_t* flags = (const int32_t*)t->h_pinned;
-    for (int k = first; k < last; ++k) {
-      if (flags[k - first] == 0) {
-        done = true;
-        break;
-      }
-      d = k;
-    }
+  for (int l = 1; l <= top; ++l) {
+    ProfScope ps(t, PROF_BFS, r.st, l);
+    k_bfs_level<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l);
   }
-  if (!done) return A2A_ERR_LEVEL_OVERFLOW;
   HIP_TRY(hipGetLastError());
-  // how full each level is decides which kernel flavour the passes use
-  try {
-    std::vector<long long> lt((size_t)gv.G * L.Lcap);
-    HIP_TRY(hipMemcpyAsync(lt.data(), gv.ltot, lt.size() * 8, hipMemcpyDeviceToHost, r.st));
-    HIP_TRY(hipStreamSynchronize(r.st));
-    r.lanes_per_node.assign((size_t)d + 2, 0.0);
-    for (int g = 0; g < gv.G; ++g)
-      for (int k = 0; k <= d; ++k) r.lanes_per_node[k] += (double)lt[(size_t)g * L.Lcap + k];
-    if (t->prof_mode)
+  r.lanes_per_node.clear();
+  if (t->prof_mode) {  // profiling only: how full each level is (this is the one place that waits)
+    try {
+      std::vector<long long> lt((size_t)gv.G * L.Lcap);
+      HIP_TRY(hipMemcpyAsync(lt.data(), gv.ltot, lt.size() * 8, hipMemcpyDeviceToHost, r.st));
+      HIP_TRY(hipStreamSynchronize(r.st));
+      r.lanes_per_node.assign((size_t)L.Lcap, 0.0);
+      int d = 0;
+      for (int g = 0; g < gv.G; ++g)
+        for (int k = 0; k < L.Lcap; ++k) {
+          const long long n = lt[(size_t)g * L.Lcap + k];
+          r.lanes_per_node[k] += (double)n;
+          if (n > 0 && k > d) d = k;
+        }
       for (int k = 0; k <= d; ++k)
         t->prof_pairs_level[k < A2A_PROF_MAX_LEVELS ? k : A2A_PROF_MAX_LEVELS - 1] += (int64_t)r.lanes_per_node[k];
-    for (auto& x : r.lanes_per_node) x /= (double)gv.G * (double)t->N;
-  } catch (const std::bad_alloc&) {
-    return A2A_ERR_NO_MEMORY;
+      // which lane layout and precision each batch's kernels pick on each level (the kernels' own rule)
+      for (int g = 0; g < gv.G; ++g)
+        for (int k = 0; k + 1 < L.Lcap; ++k) {
+          const long long* row = &lt[(size_t)g * L.Lcap];
+          const long long here = row[k], after = row[k + 1], before = k > 0 ? row[k - 1] : 0;
+          if (here == 0) continue;
+          if (k >= 1 && L.values)
+            t->prof_fwd_flavours |= 1ull << (3 * pick_flavour(here, before, t->N) + (r.narrow(k) ? 0 : (r.narrow(k - 1) ? 1 : 2)));
+          if (L.loads && (r.demand != nullptr || after > 0))
+            t->prof_bwd_flavours |= 1ull << (2 * pick_flavour(here, after, t->N) + (r.narrow(k) ? 0 : 1));
+        }
+      for (auto& x : r.lanes_per_node) x /= (double)gv.G * (double)t->N;
+      if (d > t->prof_depth) t->prof_depth = d;
+      t->prof_groups++;
+    } catch (const std::bad_alloc&) {
+      return A2A_ERR_NO_MEMORY;
+    }
   }
-  *depth = d;
-  if (d > t->prof_depth) t->prof_depth = d;
-  t->prof_groups++;
   return A2A_OK;
 }
 
-// Row offsets, then sigma for levels 1..depth.
+// Row offsets, then sigma for levels 1 .. depth.
 int run_fwd(const Run& r, const GroupView& gv, int depth) {
   const a2a_topo* t = r.t;
   const Layout& L = r.L;
   {
-    // With demands the backward pass also visits the deepest level and looks at the (empty) level
-    // after it, which the BFS has computed: its index entries are written too.
+    // With demands the backward pass also visits a batch's deepest level and looks at the (empty)
+    // level after it, which the BFS has computed: its index entries are written too.
     const int idx_depth = gv.dem != nullptr ? depth + 1 : depth;
     ProfScope ps(t, PROF_OFFSETS, r.st);
     if (idx_depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * idx_depth), kWave, 0, r.st>>>(gv, idx_depth);
@@ -376,34 +350,19 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
   }
   const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
   for (int l = 1; l <= depth; ++l) {
-    const bool few = r.few(l), spread = r.fwd_spread(l);
-    ProfScope ps(t, few ? PROF_FWD_FEW : (spread ? PROF_FWD_SPREAD : PROF_FWD), r.st, l);
+    const int cls = r.few(l) ? PROF_FWD_FEW : (r.few(l - 1) ? PROF_FWD_SPREAD : PROF_FWD);
+    ProfScope ps(t, cls, r.st, l);
     const bool count = t->prof_mode == 2;
-    // the deepest level's coef is 1/sigma: the forward launch leaves it there
-    const bool init_coef = gv.coef != nullptr && l == depth && gv.dem == nullptr;
     auto launch = [&](auto kernel) {
-      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, init_coef, r.misc());
+      kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
     };
-    // precision of the level gathered from (tin) and of the one written (tout)
-    auto pick = [&](auto tin, auto tout) {
-      using TIn = decltype(tin);
-      using TOut = decltype(tout);
-      if (spread)
-        count ? launch(k_fwd_spread<true, TIn, TOut>) : launch(k_fwd_spread<false, TIn, TOut>);
-      else if (!few)
-        count ? launch(k_fwd_level<true, TIn, TOut>) : launch(k_fwd_level<false, TIn, TOut>);
-      else if (r.slots(l))
-        count ? launch(k_fwd_few<true, true, TIn, TOut>) : launch(k_fwd_few<false, true, TIn, TOut>);
-      else
-        count ? launch(k_fwd_few<true, false, TIn, TOut>) : launch(k_fwd_few<false, false, TIn, TOut>);
-    };
-    if (r.narrow(l)) {
-      pick(float{}, float{});
-    } else if (r.narrow(l - 1)) {
-      pick(float{}, double{});
-    } else {
-      pick(double{}, double{});
-    }
+    // precision of the level gathered from and of the one written
+    if (r.narrow(l))
+      count ? launch(k_fwd<true, float, float>) : launch(k_fwd<false, float, float>);
+    else if (r.narrow(l - 1))
+      count ? launch(k_fwd<true, float, double>) : launch(k_fwd<false, float, double>);
+    else
+      count ? launch(k_fwd<true, double, double>) : launch(k_fwd<false, double, double>);
     if (t->prof_mode != 0 && l < 64 && r.narrow(l - 1)) t->prof_narrow |= 1ull << l;
   }
   HIP_TRY(hipGetLastError());
@@ -427,6 +386,59 @@ int run_fold(const Run& r, const GroupView& gv, int depth) {
   k_fold_counters<<<1, kBlock, 0, r.st>>>(gv, depth, r.misc());
   HIP_TRY(hipGetLastError());
   return A2A_OK;
+}
+
+// Largest finite hop distance of the topology: the BFS from every node, 64 sources per mask, as
+// many super-batches at a time as about 1 GiB of temporary device memory holds.  Runs on the
+// default stream and waits (this is a2a_topo_create).
+int probe_depth(const a2a_topo* t, int32_t* depth_out) {
+  const int N = t->N;
+  const int Npad = (int)align_up((size_t)N, kBlock);
+  const int nb64 = Npad / kBfsNodes;
+  const int sb_all = ((N + 63) / 64 + kSub - 1) / kSub;
+  const size_t per_sb = (size_t)Npad * kSub * 8;  // one mask array of one super-batch
+  const int sb_grp = (int)std::max<size_t>(1, std::min<size_t>((size_t)sb_all, ((size_t)1 << 30) / (3 * per_sb)));
+  constexpr int kChunk = 16;  // levels between two looks at the "anything new" flags
+  uint64_t* buf = nullptr;
+  int* d_flags = nullptr;
+  int h_flags[kChunk];
+  int rc = A2A_OK, deepest = 0;
+  if (hipMalloc((void**)&buf, 3 * per_sb * sb_grp) != hipSuccess ||
+      hipMalloc((void**)&d_flags, kChunk * sizeof(int)) != hipSuccess) {
+    (void)hipGetLastError();
+    if (buf) (void)hipFree(buf);
+    return A2A_ERR_HIP;
+  }
+  uint64_t* ring[2] = {buf, buf + per_sb / 8 * sb_grp};
+  uint64_t* seen = buf + 2 * (per_sb / 8) * sb_grp;
+  for (int sb0 = 0; sb0 < sb_all && rc == A2A_OK; sb0 += sb_grp) {
+    const int SB = std::min(sb_grp, sb_all - sb0);
+    k_probe_init<<<grid_for(SB, nb64), kBfsBlock, 0, nullptr>>>(ring[0], seen, N, Npad, SB, sb0 * kSub * 64);
+    int level = 1;
+    bool done = false;
+    while (!done && rc == A2A_OK) {
+      rc = zero_async(d_flags, sizeof(h_flags), nullptr) == hipSuccess ? A2A_OK : A2A_ERR_HIP;
+      for (int k = 0; k < kChunk && rc == A2A_OK; ++k)
+        k_probe_level<<<grid_for(SB, nb64), kBfsBlock, 0, nullptr>>>(t->d_in_ptr, t->d_in_col, ring[(level + k + 1) & 1],
+                                                                   ring[(level + k) & 1], seen, N, Npad, SB, d_flags + k);
+      if (rc == A2A_OK && (hipGetLastError() != hipSuccess ||
+                           hipMemcpy(h_flags, d_flags, sizeof(h_flags), hipMemcpyDeviceToHost) != hipSuccess))
+        rc = A2A_ERR_HIP;
+      for (int k = 0; k < kChunk && rc == A2A_OK && !done; ++k) {
+        if (h_flags[k] == 0)
+          done = true;  // level + k reached nothing new: every later level is empty too
+        else
+          deepest = std::max(deepest, level + k);
+      }
+      level += kChunk;
+      if (level > N) done = true;  // a shortest path has at most N - 1 links
+    }
+  }
+  (void)hipFree(buf);
+  (void)hipFree(d_flags);
+  if (rc != A2A_OK) (void)hipGetLastError();
+  *depth_out = deepest;
+  return rc;
 }
 
 int check_common(const a2a_topo* t, int32_t src_begin, int32_t src_count, void* ws) {
@@ -483,10 +495,6 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
     for (int32_t u = 0; u < N; ++u)  // ascending link id => in-lists are stable in link order
       for (int32_t p = row_ptr[u]; p < row_ptr[u + 1]; ++p) in_col[(size_t)fill[col_idx[p]]++] = u;
     for (int32_t v = 0; v < N; ++v) t->dmax_in = std::max(t->dmax_in, in_ptr[(size_t)v + 1] - in_ptr[v]);
-    const int e_out = host_ecc0(N, row_ptr, col_idx);
-    const int e_in = host_ecc0(N, in_ptr.data(), in_col.data());
-    t->level_bound = (e_out >= 0 && e_in >= 0) ? e_out + e_in : N - 1;
-    if (t->level_bound > N - 1) t->level_bound = N - 1;
   } catch (const std::bad_alloc&) {
     delete t;
     return A2A_ERR_NO_MEMORY;
@@ -496,19 +504,21 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
   t->dmax = dmax;
   const size_t pb = ((size_t)N + 1) * sizeof(int32_t);
   const size_t cb = (size_t)(E > 0 ? E : 1) * sizeof(int32_t);
+  const size_t slot_bytes = (size_t)a2a_topo::kSlots * a2a_topo::kSlotWords * sizeof(int64_t);
   bool ok = hipMalloc((void**)&t->d_out_ptr, pb) == hipSuccess &&
             hipMalloc((void**)&t->d_out_col, cb) == hipSuccess &&
             hipMalloc((void**)&t->d_in_ptr, pb) == hipSuccess &&
             hipMalloc((void**)&t->d_in_col, cb) == hipSuccess &&
-            hipMalloc((void**)&t->d_small, 16 * sizeof(int64_t)) == hipSuccess &&
-            hipHostMalloc((void**)&t->h_pinned, 16 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
+            hipMalloc((void**)&t->d_small, slot_bytes) == hipSuccess &&
+            hipHostMalloc((void**)&t->h_pinned, slot_bytes, hipHostMallocDefault) == hipSuccess;
   ok = ok && hipGetSymbolAddress(&t->d_scratch, HIP_SYMBOL(scratch)) == hipSuccess && t->d_scratch != nullptr;
-  ok = ok && hipMemset(t->d_small, 0, 16 * sizeof(int64_t)) == hipSuccess &&
+  ok = ok && hipMemset(t->d_small, 0, slot_bytes) == hipSuccess &&
        hipMemcpy(t->d_out_ptr, row_ptr, pb, hipMemcpyHostToDevice) == hipSuccess &&
        hipMemcpy(t->d_in_ptr, in_ptr.data(), pb, hipMemcpyHostToDevice) == hipSuccess;
   if (ok && E > 0)
     ok = hipMemcpy(t->d_out_col, col_idx, (size_t)E * 4, hipMemcpyHostToDevice) == hipSuccess &&
          hipMemcpy(t->d_in_col, in_col.data(), (size_t)E * 4, hipMemcpyHostToDevice) == hipSuccess;
+  if (ok && E > 0) ok = probe_depth(t, &t->level_bound) == A2A_OK;
   if (!ok) {
     (void)hipGetLastError();
     a2a_topo_destroy(t);
@@ -575,8 +585,8 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
   const int tiles = L.Npad / kWave;
   for (int b0 = 0; b0 < nb; b0 += L.G) {
     const GroupView gv = r.view(b0, nb - b0 < L.G ? nb - b0 : L.G);
-    int depth = 0;
-    rc = run_bfs(r, gv, &depth);
+    const int depth = t->level_bound;
+    rc = run_bfs(r, gv, depth);
     if (rc != A2A_OK) return rc;
     if (sigma) {
       rc = run_fwd(r, gv, depth);
@@ -601,7 +611,7 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
   k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), nullptr, (long long*)unreachable,
                              (long long*)flags);
   HIP_TRY(hipGetLastError());
-  t->prof_calls++;
+  if (t->prof_mode) t->prof_calls++;
   return A2A_OK;
 }
 
@@ -636,8 +646,8 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
   const int nb = (src_count + 63) / 64;
   for (int b0 = 0; b0 < nb; b0 += L.G) {
     const GroupView gv = r.view(b0, nb - b0 < L.G ? nb - b0 : L.G);
-    int depth = 0;
-    rc = run_bfs(r, gv, &depth);
+    const int depth = t->level_bound;
+    rc = run_bfs(r, gv, demand ? depth + 1 : depth);
     if (rc != A2A_OK) return rc;
     rc = run_fwd(r, gv, depth);
     if (rc != A2A_OK) return rc;
@@ -645,31 +655,21 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
       HIP_TRY(zero_async(gv.part, (size_t)gv.G * L.Epad * 8, st));
       if (demand) HIP_TRY(zero_async(gv.wpart, (size_t)gv.G * L.nb64 * 8, st));
       const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
-      // Unit demands: the deepest level has no successors and its coef = 1/sigma was left by the
-      // forward pass, nothing to add.  With demands it is visited like the others.
+      // Unit demands: a batch's deepest level has no successors and its coef = 1/sigma was left by
+      // the forward pass, nothing to add (the kernel skips it).  With demands it is visited like the others.
       for (int l = demand ? depth : depth - 1; l >= 0; --l) {
-        const bool spread = r.bwd_spread(l, depth);
-        ProfScope ps(t, r.few(l) ? PROF_BWD_FEW : (spread ? PROF_BWD_SPREAD : PROF_BWD), st, l);
+        const int cls = r.few(l) ? PROF_BWD_FEW : (r.few(l + 1) ? PROF_BWD_SPREAD : PROF_BWD);
+        ProfScope ps(t, cls, st, l);
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
-        auto pick = [&](auto ts, auto with_demand) {  // precision of this level's sigma
-          using TS = decltype(ts);
-          constexpr bool kDemand = decltype(with_demand)::value;
-          if (spread)
-            launch(k_bwd_spread<TS, kDemand>);
-          else if (!r.few(l))
-            launch(k_bwd_level<TS, kDemand>);
-          else if (r.slots(l))
-            launch(k_bwd_few<true, TS, kDemand>);
-          else
-            launch(k_bwd_few<false, TS, kDemand>);
-        };
-        if (demand)
-          r.narrow(l) ? pick(float{}, std::true_type{}) : pick(double{}, std::true_type{});
+        if (demand)  // precision of this level's sigma
+          r.narrow(l) ? launch(k_bwd<float, true>) : launch(k_bwd<double, true>);
         else
-          r.narrow(l) ? pick(float{}, std::false_type{}) : pick(double{}, std::false_type{});
+          r.narrow(l) ? launch(k_bwd<float, false>) : launch(k_bwd<double, false>);
       }
-      if (demand && weighted_dist)
-        k_fold_weighted<<<1, kBlock, 0, st>>>(gv.wpart, (long long)gv.G * L.nb64, weighted_dist);
+      if (demand && weighted_dist) {
+        k_fold_weighted_batch<<<(unsigned)gv.G, kBlock, 0, st>>>(gv.wpart, L.nb64);
+        k_fold_weighted<<<1, 64, 0, st>>>(gv.wpart, gv.G, L.nb64, weighted_dist);
+      }
       ProfScope ps(t, PROF_REDUCE, st);
       k_reduce_part<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(
           gv.part, L.Epad, gv.G, (long long)t->E, b0 == 0 ? 1 : 0, load);
@@ -680,7 +680,7 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
   k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), (long long*)dist_sum_total,
                              nullptr, (long long*)flags);
   HIP_TRY(hipGetLastError());
-  t->prof_calls++;
+  if (t->prof_mode) t->prof_calls++;
   return A2A_OK;
 }
 
@@ -718,16 +718,19 @@ int a2a_schedule_bound(const a2a_topo* t, const double* load, int64_t sum_dist, 
   if (!t || !out || !load || t->E <= 0 || !(m_bytes > 0.0) || !(b_bytes_per_s > 0.0) || sum_dist < 0)
     return A2A_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
-  k_load_extrema<<<1, 1024, 0, st>>>(load, (long long)t->E, (long long*)t->d_small);
+  const size_t slot = (size_t)(t->next_slot.fetch_add(1) % a2a_topo::kSlots) * a2a_topo::kSlotWords;
+  int64_t* d_res = t->d_small + slot;
+  const int64_t* h_res = t->h_pinned + slot;
+  k_load_extrema<<<1, 1024, 0, st>>>(load, (long long)t->E, (long long*)d_res);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(t->h_pinned, t->d_small, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync((void*)h_res, d_res, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   double lmax, lmin;
-  std::memcpy(&lmax, &t->h_pinned[0], 8);
-  std::memcpy(&lmin, &t->h_pinned[2], 8);
+  std::memcpy(&lmax, &h_res[0], 8);
+  std::memcpy(&lmin, &h_res[2], 8);
   const double m = m_bytes, b = b_bytes_per_s;
   out->max_load = lmax;
-  out->argmax_arc = t->h_pinned[1];
+  out->argmax_arc = h_res[1];
   out->min_load = lmin;
   out->sum_dist = sum_dist;
   out->n_links = t->E;
@@ -749,19 +752,22 @@ int a2a_schedule_bound_cap(const a2a_topo* t, const double* load, const double* 
   if (!t || !out || !load || !cap || t->E <= 0 || !(m_bytes > 0.0) || !(b_bytes_per_s > 0.0) || sum_dist < 0)
     return A2A_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
-  k_util_extrema<<<1, 1024, 0, st>>>(t->d_out_ptr, load, cap, t->N, (long long*)t->d_small);
+  const size_t slot = (size_t)(t->next_slot.fetch_add(1) % a2a_topo::kSlots) * a2a_topo::kSlotWords;
+  int64_t* d_res = t->d_small + slot;
+  const int64_t* h_res = t->h_pinned + slot;
+  k_util_extrema<<<1, 1024, 0, st>>>(t->d_out_ptr, load, cap, t->N, (long long*)d_res);
   HIP_TRY(hipGetLastError());
-  HIP_TRY(hipMemcpyAsync(t->h_pinned, t->d_small, 6 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync((void*)h_res, d_res, 6 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  if (t->h_pinned[5] != 0) return A2A_ERR_INVALID_ARG;  // a capacity that is not positive and finite
+  if (h_res[5] != 0) return A2A_ERR_INVALID_ARG;  // a capacity that is not positive and finite
   double umax, umin, total, cmax;
-  std::memcpy(&umax, &t->h_pinned[0], 8);
-  std::memcpy(&umin, &t->h_pinned[2], 8);
-  std::memcpy(&total, &t->h_pinned[3], 8);
-  std::memcpy(&cmax, &t->h_pinned[4], 8);
+  std::memcpy(&umax, &h_res[0], 8);
+  std::memcpy(&umin, &h_res[2], 8);
+  std::memcpy(&total, &h_res[3], 8);
+  std::memcpy(&cmax, &h_res[4], 8);
   const double m = m_bytes, b = b_bytes_per_s;
   out->max_util = umax;
-  out->argmax_arc = t->h_pinned[1];
+  out->argmax_arc = h_res[1];
   out->min_util = umin;
   out->sum_dist = sum_dist;
   out->n_links = t->E;
@@ -811,6 +817,7 @@ int a2a_profile_enable(a2a_topo* t, int mode) {
   t->prof_depth = 0;
   t->prof_groups = 0;
   t->prof_narrow = 0;
+  t->prof_fwd_flavours = t->prof_bwd_flavours = 0;
   t->prof_mode = mode;
   std::memset(t->prof_pairs_level, 0, sizeof(t->prof_pairs_level));
   std::memset(t->prof_dag_level, 0, sizeof(t->prof_dag_level));
@@ -841,6 +848,8 @@ int a2a_profile_read(a2a_topo* t, a2a_profile* out) {
   out->depth = t->prof_depth;
   out->groups = t->prof_groups;
   out->narrow_levels = t->prof_narrow;
+  out->fwd_flavours = t->prof_fwd_flavours;
+  out->bwd_flavours = t->prof_bwd_flavours;
   return A2A_OK;
 }
 

@@ -258,8 +258,7 @@ def test_gpu_demand_source_ranges_groups_and_reruns(oracle):
     assert np.array_equal(full[0], again[0]) and full[1] == again[1]  # run-to-run bitwise
     least = topo.workspace_bytes(N, a2a.WS_LOADS | a2a.WS_MINIMAL)
     small = run_demand_gpu(topo, dem, max_ws=least)  # one super-batch at a time: several groups
-    np.testing.assert_allclose(small[0], full[0], rtol=1e-12)
-    assert small[1] == pytest.approx(full[1], rel=1e-13)
+    assert np.array_equal(small[0], full[0]) and small[1] == full[1]  # the grouping changes no bit
     # a source range that starts and ends inside a batch
     part, part_wd = oracle.run_demand(rp, col, dem[70:203], 70)
     got = run_demand_gpu(topo, dem[70:203], 70)

@@ -21,12 +21,13 @@ def a2a():
     return lib
 
 
-def layered_collisions():
-    """64 sources -> 40 nodes (A) -> 8 nodes (B) -> 1..8 leaves each, plus filler nodes with a link into
+def layered_collisions(B=8):
+    """64 sources -> 40 nodes (A) -> B nodes -> 1..B leaves each, plus filler nodes with a link into
     the sources.  Level 1 holds A with all 64 sources per node, level 2 is sparse on average but every
-    node of A has 8 successors there for every source: the backward pass of level 1 adds 8 different
-    coef values per (node, source), which is where the order of additions could show."""
-    S, A, B = 64, 40, 8
+    node of A has B successors there for every source: the backward pass of level 1 adds B different
+    coef values per (node, source), which is where the order of additions could show.  With B = 12 the
+    nodes of A have more than eight out-links (a second tile of links into the same accumulators)."""
+    S, A = 64, 40
     a0, b0 = S, S + A
     c0 = b0 + B
     leaves = sum(range(1, B + 1))
@@ -117,6 +118,7 @@ SMALL.update({
     # path counts from node 0 are tiny, from node 1 they reach 2^30
     "late_blowup": gen.csr_from_rows([[]] + [[i + 1, i + 1] for i in range(1, 31)] + [[]]),
     "layered_collisions": layered_collisions(),
+    "layered_collisions_wide": layered_collisions(12),
     "dense_layers": dense_layers(),
 })
 
@@ -302,30 +304,30 @@ def test_c5_full_distance_matrix_bit_exact(a2a, oracle):
 
 
 def test_workspace_size_and_reruns(a2a, oracle):
-    """One batch at a time vs all batches together: same integers, loads equal to rounding (which
-    kernel flavour a level gets depends on how full it is over the batches that advance together,
-    so the summation order may differ); same workspace twice: bitwise-same loads."""
+    """One batch at a time vs several vs all batches together, and the same workspace twice: the same bits
+    every time (every batch picks its lane layouts from its own level sizes, every sum has a fixed order)."""
     rp, col = gen.random_regular(1000, 6, 21)
     topo = a2a.Topology(rp, col)
     full = run_link_loads(topo)
     least = topo.workspace_bytes(topo.N, a2a.WS_LOADS | a2a.WS_MINIMAL)
     one = run_link_loads(topo, max_ws=least)
     three = run_link_loads(topo, max_ws=3 * least)
-    np.testing.assert_allclose(one[0], full[0], rtol=1e-12)
-    np.testing.assert_allclose(three[0], full[0], rtol=1e-12)
+    assert np.array_equal(one[0], full[0])
+    assert np.array_equal(three[0], full[0])
     assert full[1:] == one[1:] == three[1:]
     for ws in (None, least, 3 * least):  # run-to-run bitwise determinism
         a = run_link_loads(topo, max_ws=ws)
         b = run_link_loads(topo, max_ws=ws)
         assert np.array_equal(a[0], b[0])
-    # the same where eight different values are added per (node, source) in one LDS instruction
-    rp2, col2 = SMALL["layered_collisions"]
-    topo2 = a2a.Topology(rp2, col2)
-    first = run_link_loads(topo2, 0, 64)  # the 64 designed sources alone: one batch, levels as described
-    assert_loads_close(first[0], oracle.run(rp2, col2, 0, 64).load)
-    for _ in range(5):
-        assert np.array_equal(run_link_loads(topo2, 0, 64)[0], first[0])
-    topo2.close()
+    # the same where eight or twelve different values are added per (node, source)
+    for name in ("layered_collisions", "layered_collisions_wide"):
+        rp2, col2 = SMALL[name]
+        topo2 = a2a.Topology(rp2, col2)
+        first = run_link_loads(topo2, 0, 64)  # the 64 designed sources alone: one batch, levels as described
+        assert_loads_close(first[0], oracle.run(rp2, col2, 0, 64).load)
+        for _ in range(3):
+            assert np.array_equal(run_link_loads(topo2, 0, 64)[0], first[0])
+        topo2.close()
     d_full = run_distances(topo)
     d_one = run_distances(topo, max_ws=topo.workspace_bytes(topo.N, a2a.WS_SIGMA | a2a.WS_MINIMAL))
     for x, y in zip(d_full[:3], d_one[:3]):
@@ -445,9 +447,12 @@ def test_disabled_links_and_hosts(a2a, oracle):
             topo.close()
 
 
+LAYOUTS = ("rows", "spread", "node_source", "node_link")
+
+
 def _flavours(a2a, rp, col, src_count=None):
-    """Which kernel flavour each level got, read off the per-level launch times, with the precision of the
-    path counts it read and wrote (f = single, d = double)."""
+    """Which lane layout each batch picked on each level, with the precision of the path counts it read and
+    wrote (f = single, d = double): the library's profile reports them from the batches' own level sizes."""
     import torch
     topo = a2a.Topology(rp, col)
     cnt = topo.N if src_count is None else src_count
@@ -457,24 +462,14 @@ def _flavours(a2a, rp, col, src_count=None):
     topo.link_loads(0, cnt, load=load, workspace=ws)
     p = topo.profile_read()
     topo.profile_enable(0)
-    nb = (cnt + 63) // 64
     seen = set()
-    top = min(p["depth"], 62)  # the profile keeps 64 levels, the last one a catch-all
-    narrow = [True] + [bool((p["narrow_levels"] >> (l + 1)) & 1) for l in range(top + 1)]  # narrow[l]: level l in single
-    for l in range(top + 1):
-        lanes = p["pairs_level"][l] / (nb * topo.N)
-        ran = {k: p[k]["ms_level"][l] > 0 for k in ("fwd_rows", "fwd_few", "fwd_spread", "bwd_rows", "bwd_few", "bwd_spread")}
-        layout = "_node_source" if lanes >= 2.0 else "_node_link"
-        fwd = "_" + ("f" if l >= 1 and narrow[l - 1] else "d") + ("f" if narrow[l] else "d")
-        bwd = "_f" if narrow[l] else "_d"
-        if l == top:  # whether the deepest level seen is narrow is not in the bit mask
-            fwd = bwd = None
-        for k, name in (("fwd_rows", "fwd_rows"), ("fwd_few", "fwd_few" + layout), ("fwd_spread", "fwd_spread")):
-            if ran[k] and fwd:
-                seen.add(name + fwd)
-        for k, name in (("bwd_rows", "bwd_rows"), ("bwd_few", "bwd_few" + layout), ("bwd_spread", "bwd_spread")):
-            if ran[k] and bwd:
-                seen.add(name + bwd)
+    for i, layout in enumerate(LAYOUTS):
+        for j, prec in enumerate(("_ff", "_fd", "_dd")):
+            if (p["fwd_flavours"] >> (3 * i + j)) & 1:
+                seen.add("fwd_" + layout + prec)
+        for j, prec in enumerate(("_f", "_d")):
+            if (p["bwd_flavours"] >> (2 * i + j)) & 1:
+                seen.add("bwd_" + layout + prec)
     topo.close()
     return seen
 
@@ -496,7 +491,6 @@ def test_parity_set_reaches_every_kernel_flavour(a2a):
         got = _flavours(a2a, *funnel_layers(*FUNNELS[name]), src_count=64)
         print(name, sorted(got), flush=True)
         seen |= got
-    want = {f + p for f in ("fwd_rows", "fwd_few_node_link", "fwd_few_node_source", "fwd_spread")
-            for p in ("_ff", "_fd", "_dd")}
-    want |= {f + p for f in ("bwd_rows", "bwd_few_node_link", "bwd_few_node_source", "bwd_spread") for p in ("_f", "_d")}
+    want = {"fwd_" + f + p for f in LAYOUTS for p in ("_ff", "_fd", "_dd")}
+    want |= {"bwd_" + f + p for f in LAYOUTS for p in ("_f", "_d")}
     assert want <= seen, sorted(want - seen)
