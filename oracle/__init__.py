@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     bound,
     bound_cap,
     tree_sum,
+    sssp,
     OracleResult,
     BOUND_FIELDS,
     CAP_FIELDS,

@@ -256,6 +256,104 @@ int a2a_oracle_run_demand(int32_t N, const int32_t* row_ptr, const int32_t* col,
 }
 
 /*
+ * Single-path baseline "SSSP" (Sec. 5.2): a heuristic that computes shortest paths iteration by
+ * iteration through a graph whose link weights reflect the congestion that the earlier
+ * iterations have caused; every commodity gets ONE path.  The paper gives neither the weights
+ * nor what an iteration is; the reading taken here (parity unpinned against the paper, pinned
+ * by the invariants and the path enumeration of tests/test_sssp.py):
+ *   - an iteration routes the commodities of `iter_sources` consecutive sources (1 = source by
+ *     source, the classic form of the heuristic) against the weights it starts with;
+ *   - the weight of link a in an iteration is W[a] = number of commodities that the earlier
+ *     iterations routed over a (0 for all links in the first one);
+ *   - the path of commodity (s,t) is a path of D(s,t) links (hop count comes first: the baseline
+ *     is a shortest-path scheme like EwSP), among those one of least total weight, among those
+ *     the one whose last link has the lowest id, then the one before it, and so on; this is
+ *     what the recursion cost(s,w) = min over links a=(u,w) with D(s,u)+1 = D(s,w) of
+ *     cost(s,u) + W[a], ties to the lowest a, computes, and the paths of one source form a tree;
+ *   - after the iteration every link's load grows by the number of paths of the iteration over it.
+ * load[a] (int64, overwritten) = number of the commodities with source in
+ * src_begin .. src_begin+src_count-1 routed over a; iterations take the sources in ascending
+ * order.  dist_sum (may be NULL): [src_count] sum_t D(s,t); *unreachable (may be NULL): pairs
+ * without a path (they are not routed).  Serial.  Returns 0, or -1 on bad arguments /
+ * allocation failure.
+ */
+int a2a_oracle_sssp(int32_t N, const int32_t* row_ptr, const int32_t* col, int32_t src_begin,
+                    int32_t src_count, int32_t iter_sources, int64_t* load, int64_t* dist_sum,
+                    int64_t* unreachable) {
+  if (N <= 0 || !row_ptr || !load || src_begin < 0 || src_count < 0 || iter_sources < 1 ||
+      src_begin + (int64_t)src_count > N)
+    return -1;
+  int64_t E = row_ptr[N];
+  if (E > 0 && !col) return -1;
+  size_t En = (size_t)(E > 0 ? E : 1);
+  int32_t* dist = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  int32_t* order = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  int64_t* cost = (int64_t*)malloc(sizeof(int64_t) * (size_t)N);
+  int64_t* pred = (int64_t*)malloc(sizeof(int64_t) * (size_t)N); /* link id into the node, -1 none */
+  int64_t* sub = (int64_t*)malloc(sizeof(int64_t) * (size_t)N);  /* paths that end in or pass the node */
+  int32_t* tail = (int32_t*)malloc(sizeof(int32_t) * En);        /* node a link leaves from */
+  int64_t* weight = (int64_t*)malloc(sizeof(int64_t) * En);
+  int rc = (!dist || !order || !cost || !pred || !sub || !tail || !weight) ? -1 : 0;
+  int64_t unr = 0;
+  if (rc == 0) {
+    for (int32_t u = 0; u < N; ++u)
+      for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) tail[a] = u;
+    memset(load, 0, sizeof(int64_t) * (size_t)E);
+    for (int32_t s0 = src_begin; s0 < src_begin + src_count; s0 += iter_sources) {
+      int32_t s1 = s0 + iter_sources;
+      if (s1 > src_begin + src_count) s1 = src_begin + src_count;
+      memcpy(weight, load, sizeof(int64_t) * (size_t)E); /* what the earlier iterations left */
+      for (int32_t s = s0; s < s1; ++s) {
+        int32_t head = 0, tl = 0;
+        int64_t ds = 0;
+        for (int32_t v = 0; v < N; ++v) {
+          dist[v] = -1;
+          pred[v] = -1;
+          cost[v] = 0;
+          sub[v] = 1;
+        }
+        dist[s] = 0;
+        order[tl++] = s;
+        while (head < tl) { /* FIFO order = level order: cost[u] is final when u is taken out */
+          int32_t u = order[head++];
+          for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) {
+            int32_t w = col[a];
+            if (dist[w] < 0) {
+              dist[w] = dist[u] + 1;
+              ds += dist[w];
+              order[tl++] = w;
+            }
+            if (dist[w] == dist[u] + 1) {
+              int64_t c = cost[u] + weight[a];
+              if (pred[w] < 0 || c < cost[w] || (c == cost[w] && a < pred[w])) {
+                cost[w] = c;
+                pred[w] = a;
+              }
+            }
+          }
+        }
+        for (int32_t i = tl - 1; i >= 1; --i) { /* deepest first: sub[w] is final when w is met */
+          int32_t w = order[i];
+          load[pred[w]] += sub[w];
+          sub[tail[pred[w]]] += sub[w];
+        }
+        if (dist_sum) dist_sum[s - src_begin] = ds;
+        unr += (int64_t)N - tl;
+      }
+    }
+  }
+  if (unreachable) *unreachable = unr;
+  free(dist);
+  free(order);
+  free(cost);
+  free(pred);
+  free(sub);
+  free(tail);
+  free(weight);
+  return rc;
+}
+
+/*
  * Schedule figures from the link loads.  out[] (10 doubles):
  *  0 max link load Lmax          (all-to-all time under unit demand/capacity, Sec. 5.3)
  *  1 lowest link id attaining it

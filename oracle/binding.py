@@ -55,6 +55,10 @@ def _load():
         lib.a2a_oracle_run_demand.argtypes = [
             ctypes.c_int32, i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.POINTER(ctypes.c_double)]
+        lib.a2a_oracle_sssp.restype = ctypes.c_int
+        lib.a2a_oracle_sssp.argtypes = [
+            ctypes.c_int32, i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64)]
         lib.a2a_oracle_tree_sum.restype = ctypes.c_int64
         lib.a2a_oracle_tree_sum.argtypes = [ctypes.c_int32, ctypes.c_int32]
         _lib = lib
@@ -164,3 +168,21 @@ def run_demand(row_ptr, col_idx, demand, src_begin: int = 0):
     if rc != 0:
         raise ValueError("a2a_oracle_run_demand rejected its arguments")
     return load, wd.value
+
+
+def sssp(row_ptr, col_idx, src_begin: int = 0, src_count: Optional[int] = None, iter_sources: int = 1):
+    """Single-path SSSP baseline: (load int64[E], dist_sum int64[src_count], unreachable pairs)."""
+    lib = _load()
+    row_ptr, rp = _i32(row_ptr)
+    col_idx, cp = _i32(col_idx)
+    N = len(row_ptr) - 1
+    if src_count is None:
+        src_count = N - src_begin
+    load = np.zeros(int(row_ptr[-1]), dtype=np.int64)
+    dist_sum = np.zeros(src_count, dtype=np.int64)
+    unr = ctypes.c_int64(0)
+    rc = lib.a2a_oracle_sssp(N, rp, cp, int(src_begin), int(src_count), int(iter_sources), load.ctypes.data,
+                             dist_sum.ctypes.data, ctypes.byref(unr))
+    if rc != 0:
+        raise ValueError("a2a_oracle_sssp rejected its arguments")
+    return load, dist_sum, unr.value

@@ -81,3 +81,33 @@ def ewsp(row_ptr, col_idx):
             for a, f in flows.items():
                 load[a] = load[a] + f
     return D, sigma, load, per_commodity
+
+
+def sssp(row_ptr, col_idx, iter_sources: int = 1, src_begin: int = 0, src_count=None):
+    """Single-path SSSP baseline (Sec. 5.2) by enumeration: returns (load, chosen) with load[a] the number
+    of commodities routed over link a and chosen[(s,t)] the link sequence picked for the pair.
+
+    Iterations take `iter_sources` consecutive sources; within one, the weight of a link is the number of
+    commodities routed over it by the earlier iterations.  For every pair all link sequences of D(s,t) links
+    are written out and the one of least total weight is taken; among equals the one with the lowest last
+    link id, then the lowest link before it, and so on (the sequences are compared back to front)."""
+    row_ptr = [int(x) for x in row_ptr]
+    col_idx = [int(x) for x in col_idx]
+    N = len(row_ptr) - 1
+    if src_count is None:
+        src_count = N - src_begin
+    D = distances_by_relaxation(row_ptr, col_idx)
+    load = [0] * row_ptr[-1]
+    chosen: Dict[Tuple[int, int], Tuple[int, ...]] = {}
+    for s0 in range(src_begin, src_begin + src_count, iter_sources):
+        weight = list(load)
+        for s in range(s0, min(s0 + iter_sources, src_begin + src_count)):
+            for t in range(N):
+                if t == s or D[s][t] < 0:
+                    continue
+                paths = shortest_paths(row_ptr, col_idx, D, s, t)
+                best = min(paths, key=lambda p: (sum(weight[a] for a in p), tuple(reversed(p))))
+                chosen[(s, t)] = best
+                for a in best:
+                    load[a] += 1
+    return load, chosen
