@@ -20,9 +20,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
-KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd_level",
-               "fwd_few": "k_fwd_few", "fwd_spread": "k_fwd_spread", "bwd_rows": "k_bwd_level",
-               "bwd_few": "k_bwd_few", "bwd_spread": "k_bwd_spread", "reduce": "k_reduce_part"}
+# Profile classes of the library -> the kernel that runs them.  One k_fwd / k_bwd launch serves a level of
+# every batch; the class says which lane layout the level's size stands for (every batch picks its own).
+KERNEL_NAME = {"bfs": "k_bfs_level", "offsets": "k_write_offsets", "fwd_rows": "k_fwd[rows]",
+               "fwd_few": "k_fwd[few]", "fwd_spread": "k_fwd[spread]", "bwd_rows": "k_bwd[rows]",
+               "bwd_few": "k_bwd[few]", "bwd_spread": "k_bwd[spread]", "reduce": "k_reduce_part"}
+FWD_CLASSES = ("fwd_rows", "fwd_few", "fwd_spread")
+BWD_CLASSES = ("bwd_rows", "bwd_few", "bwd_spread")
 
 
 def algorithmic_bytes(prof, dag_level, nb, E, steps):
@@ -62,14 +66,47 @@ def algorithmic_bytes(prof, dag_level, nb, E, steps):
     return out
 
 
-def read_traffic(kernel):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "c5_pmc_traffic.txt")
+def layout_bytes(prof, dag_level, nb, E, steps, narrow_levels):
+    """The same count with the bytes the chosen layout moves: path counts of a level kept in single precision
+    (bit l+1 of narrow_levels: level l is) cost 4 bytes where the algorithmic count has 8."""
+    L = len(prof["pairs_level"])
+    narrow = [True] + [bool((narrow_levels >> (l + 1)) & 1) for l in range(L - 1)]
+    total = 16.0 * nb * E
+    for l in range(L):
+        pairs = prof["pairs_level"][l] / steps
+        sig = 4 if narrow[l] else 8
+        total += pairs * (2 + 2 * sig + 8)
+        total += dag_level[l] * ((4 if (l == 0 or narrow[l - 1]) else 8) + 8)
+    return total
+
+
+def read_traffic(config, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this configuration
+    (profiles/<config>_pmc_traffic.txt), or None if there is none."""
+    path = os.path.join(ROOT, "profiles", config.lower() + "_pmc_traffic.txt")
     if not os.path.exists(path):
         return None
     m = re.search(r"^%s\s+traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)" % re.escape(kernel),
                   open(path).read(), flags=re.M)
     return float(m.group(1)) if m else None
+
+
+def copy_bandwidth(torch, reps=5):
+    """Plain device-to-device copy of 1 GiB (torch's copy_ = the runtime's copy kernel): GB/s of bytes read
+    plus bytes written.  What this machine's HBM gives a streaming kernel, beside the 8 TB/s data-sheet figure."""
+    src = torch.ones(2 ** 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    beg, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    beg.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    end.record()
+    torch.cuda.synchronize()
+    ms = beg.elapsed_time(end) / reps
+    del src, dst
+    return 2.0 * 2 ** 30 / (ms * 1e-3) / 1e9
 
 
 def main():
@@ -87,8 +124,8 @@ def main():
                     help="skip the a2a_link_loads_demand leg (unequal demands, reported beside the metric)")
     ap.add_argument("--max-workspace-gib", type=float, default=None)
     ap.add_argument("--pmc-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 "
-                         "FETCH_SIZE / WRITE_SIZE readings can be scaled")
+                    help="kept for old command lines: the 1 GiB device copies (known bytes, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings) now always run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (sources would shard across GPUs with one "
@@ -118,26 +155,31 @@ def main():
         # sum_dist / flags stay on the device until the end; the bound needs Lmax only
         return topo.schedule_bound(load, 0, 0, 1.0, 1.0)[0]
 
-    if args.pmc_calibration:
-        src = torch.ones(2 ** 28, dtype=torch.float32, device="cuda")  # 1 GiB read, 1 GiB written
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    copy_gbps = copy_bandwidth(torch)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    topo.profile_enable(1)
+    # timed region: K steps, nothing else (no per-launch events); an event pair per step gives the median
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         bound = step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    prof = topo.profile_read()
-    # one more, untimed, step counts the (source, link) pairs on shortest paths; its loads must be
-    # the same bits as the timed step's (fixed summation order)
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     load_timed = load.clone()
+    # untimed: per-kernel split from HIP events around every launch, on the stream the kernels run on
+    prof_steps = 2
+    topo.profile_enable(1)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = topo.profile_read()
+    # one more untimed step counts the (source, link) pairs on shortest paths; its loads must be
+    # the same bits as the timed step's (fixed summation order)
     topo.profile_enable(2)
     step()
     torch.cuda.synchronize()
@@ -151,9 +193,10 @@ def main():
     fl = int(flags.item())
     bound, _ = topo.schedule_bound(load, sum_dist, fl, 1.0, 1.0, allow_disconnected=True)
 
-    steps = args.steps
+    steps = prof_steps  # the per-kernel figures come from the profiled steps
     nb = (N + 63) // 64
     alg = algorithmic_bytes(prof, dag_level, nb, E, steps)
+    cfg = args.config
     per_kernel = {}
     for k, name in KERNEL_NAME.items():
         ms, n = prof[k]["ms"], prof[k]["launches"]
@@ -161,22 +204,31 @@ def main():
             per_kernel[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps,
                                 "avg_launch_ms": ms / n, "alg_GB_per_step": alg[k] / 1e9,
                                 "alg_GBps": alg[k] / (ms / steps * 1e-3) / 1e9 if ms > 0 else None,
-                                "traffic_bytes_per_launch": read_traffic(name),
                                 "ms_by_level": {str(l): round(x / steps, 3)
                                                 for l, x in enumerate(prof[k]["ms_level"]) if x > 0}}
-    dom = max(KERNEL_NAME, key=lambda k: prof[k]["ms"])
-    kname = KERNEL_NAME[dom]
-    n_l = prof[dom]["launches"]
-    achieved = alg[dom] * steps / n_l / (prof[dom]["ms"] / n_l * 1e-3) / 1e9
+    # The dominant kernel: k_fwd and k_bwd are one kernel each (all their levels), the others as named.
+    groups = {"k_bwd": BWD_CLASSES, "k_fwd": FWD_CLASSES, "k_bfs_level": ("bfs",),
+              "k_write_offsets": ("offsets",), "k_reduce_part": ("reduce",)}
+    g_ms = {g: sum(prof[c]["ms"] for c in cl) for g, cl in groups.items()}
+    kname = max(g_ms, key=g_ms.get)
+    n_l = sum(prof[c]["launches"] for c in groups[kname])
+    k_alg = sum(alg[c] for c in groups[kname])            # per step
+    k_ms = g_ms[kname] / steps                            # per step
+    achieved = k_alg / (k_ms * 1e-3) / 1e9
     alg_total = sum(alg.values())
-    timed_calls = max(prof["calls"], 1)
+    lay_total = layout_bytes(prof, dag_level, nb, E, steps, prof["narrow_levels"])
+    traffic = read_traffic(cfg, kname)
     roofline = {
         "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kname),
-        "alg_bytes_per_launch": alg[dom] * steps / n_l, "avg_launch_ms": prof[dom]["ms"] / n_l,
+        "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+        "alg_bytes_per_launch": k_alg * steps / n_l, "avg_launch_ms": g_ms[kname] / n_l,
         "launches_per_step": n_l / steps,
+        "copy_GBps": copy_gbps, "frac_of_copy": achieved / copy_gbps,
         "whole_path": {"alg_bytes": alg_total, "GBps": alg_total / sec / 1e9,
-                       "frac": alg_total / sec / 1e9 / HBM_PEAK_GBPS},
+                       "frac": alg_total / sec / 1e9 / HBM_PEAK_GBPS,
+                       "frac_of_copy": alg_total / sec / 1e9 / copy_gbps,
+                       "layout_bytes": lay_total, "layout_frac": lay_total / sec / 1e9 / HBM_PEAK_GBPS,
+                       "traffic": read_traffic(cfg, "whole_step")},
         "per_kernel": per_kernel,
     }
 
@@ -255,21 +307,29 @@ def main():
         tc = time.perf_counter()
         res = oracle.run(rp, col, 0, sample, threads=cores)
         tc = time.perf_counter() - tc
+        # the same on one core, on a sample sized for about 5 s from the all-core rate
+        one = int(max(1, min(N, sample * 5.0 / max(tc, 1e-4) / max(res.threads, 1))))
+        t1 = time.perf_counter()
+        oracle.run(rp, col, 0, one, threads=1)
+        t1 = time.perf_counter() - t1
         cpu = {"value": sample * E / tc, "unit": "edges/s", "cores": res.threads, "kind": "oracle",
                "sample": f"sources 0..{sample - 1} of {N} on the same CSR ({tc:.1f} s); "
                          f"serial BFS + dependency pass per source, sources split over threads",
-               "seconds": tc}
+               "seconds": tc,
+               "one_core": {"value": one * E / t1, "unit": "edges/s", "cores": 1, "seconds": t1,
+                            "sample": f"sources 0..{one - 1} of {N}"}}
 
     out = {
         "metric": "all_pairs_bfs_link_load_teps", "value": N * E / sec, "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+        "ms_per_step_median": median_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": f"{args.config}: " + {
             "C1": "8x8 torus", "C2": "hypercube n=10", "C3": "16x16x16 torus",
             "C4": "Imase-Itoh N=16384 d=4", "C5": "random 8-regular digraph N=65536 seed 1234",
         }[args.config] + ", unit all-pairs demand", "N": N, "E": E, "sources": N,
-            "workspace_GiB": ws_gib, "groups_per_step": prof["groups"] // timed_calls,
+            "workspace_GiB": ws_gib, "groups_per_step": prof["groups"] // max(prof["calls"], 1),
             "depth": prof["depth"], "dag_links": dag},
         "result": {"sum_dist": sum_dist, "max_load": bound.max_load, "argmax_arc": bound.argmax_arc,
                    "rerun_bitwise": rerun_bitwise, "ratio_to_lower_bound": bound.ratio, "flags": fl},

@@ -65,6 +65,7 @@ typedef enum a2a_status {
 #define A2A_WS_DISTANCES 0x0 /* a2a_distances without sigma */
 #define A2A_WS_SIGMA 0x1     /* a2a_distances with sigma */
 #define A2A_WS_LOADS 0x2     /* a2a_link_loads */
+#define A2A_WS_SSSP 0x4      /* a2a_sssp_loads; pass iter_sources as src_count */
 #define A2A_WS_MINIMAL 0x100 /* smallest usable size (one batch at a time) instead of the
                                 recommended one (all batches advance together) */
 
@@ -173,6 +174,34 @@ int a2a_link_loads_demand(const a2a_topo* topo, int32_t src_begin, int32_t src_c
                           const double* demand, double* load, double* weighted_dist,
                           int64_t* dist_sum_total, int64_t* flags, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Link loads of the single-path baseline "SSSP" of Sec. 5.2: a heuristic that computes shortest
+ * paths iteration by iteration through a graph whose link weights reflect the congestion caused
+ * by the earlier iterations; every commodity (s,t) is routed over ONE path.  The paper names the
+ * heuristic and cites its source but gives neither the weights nor what an iteration is; this
+ * library's reading:
+ *   - an iteration routes the commodities of iter_sources consecutive sources against the weights
+ *     it starts with; the weight of a link is the number of commodities that the earlier
+ *     iterations routed over it (0 everywhere in the first);
+ *   - the path of (s,t) has D(s,t) links (hop count first, as for EwSP), among those the least
+ *     total weight, among those the lowest id of the last link, then of the one before it, ...;
+ *     the paths from one source form a tree;
+ *   - load[a] = number of commodities with source in src_begin .. src_begin+src_count-1 routed over a.
+ *   iter_sources  a positive multiple of 64 (one or more batches of 64 sources; the iterations of
+ *                 a call are its groups of batches, in ascending source order).  Larger values
+ *                 mean fewer, cheaper iterations and weights that react later.
+ *   load          device, double[E], overwritten: whole numbers, exact
+ *   dist_sum_total, flags   as for a2a_link_loads (A2A_FLAG_SIGMA_INEXACT is never set)
+ *   workspace     device, at least a2a_workspace_bytes(topo, iter_sources, A2A_WS_SSSP) bytes: it must
+ *                 hold a whole iteration (else A2A_ERR_WORKSPACE_TOO_SMALL); more is not used
+ * Only enqueues, like a2a_link_loads.  All sums are integer: results do not depend on any order.
+ * Feed load to a2a_schedule_bound for the all-to-all time of the routing (its largest link load,
+ * Sec. 5.3).  A2A_ERR_INVALID_ARG if iter_sources is not a positive multiple of 64.
+ */
+int a2a_sssp_loads(const a2a_topo* topo, int32_t src_begin, int32_t src_count, int32_t iter_sources,
+                   double* load, int64_t* dist_sum_total, int64_t* flags, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
 
 typedef struct a2a_bound {
   double max_load;         /* Lmax: all-to-all time under unit demand and capacity (Sec. 5.3) */

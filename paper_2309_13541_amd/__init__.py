@@ -19,7 +19,7 @@ from .binding import (  # noqa: F401
     status_string,
     EXPORTED_SYMBOLS,
     STATIC_WORKSPACE_BYTES,
-    WS_DISTANCES, WS_SIGMA, WS_LOADS, WS_MINIMAL,
+    WS_DISTANCES, WS_SIGMA, WS_LOADS, WS_SSSP, WS_MINIMAL,
     FLAG_SIGMA_INEXACT, FLAG_UNREACHABLE,
     OK, ERR_INVALID_ARG, ERR_SELF_LOOP, ERR_WORKSPACE_TOO_SMALL, ERR_HIP, ERR_NOT_IMPLEMENTED,
     ERR_DISCONNECTED, ERR_NO_MEMORY, ERR_LEVEL_OVERFLOW,

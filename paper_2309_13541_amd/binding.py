@@ -31,6 +31,7 @@ ERR_LEVEL_OVERFLOW = -8
 WS_DISTANCES = 0x0
 WS_SIGMA = 0x1
 WS_LOADS = 0x2
+WS_SSSP = 0x4
 WS_MINIMAL = 0x100
 FLAG_SIGMA_INEXACT = 0x1
 FLAG_UNREACHABLE = 0x2
@@ -39,7 +40,7 @@ EXPORTED_SYMBOLS = (
     "a2a_topo_create", "a2a_topo_destroy", "a2a_topo_info", "a2a_workspace_bytes",
     "a2a_distances", "a2a_link_loads", "a2a_link_loads_demand", "a2a_schedule_bound", "a2a_status_string",
     "a2a_profile_enable", "a2a_profile_read", "a2a_tree_lower_bound", "a2a_schedule_bound_cap",
-    "a2a_link_loads_static",
+    "a2a_link_loads_static", "a2a_sssp_loads",
 )
 STATIC_WORKSPACE_BYTES = 32 << 20
 
@@ -161,6 +162,8 @@ def load_library():
     lib.a2a_link_loads.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.a2a_link_loads_static.restype = ctypes.c_int
     lib.a2a_link_loads_static.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    lib.a2a_sssp_loads.restype = ctypes.c_int
+    lib.a2a_sssp_loads.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.a2a_link_loads_demand.restype = ctypes.c_int
     lib.a2a_link_loads_demand.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.a2a_schedule_bound_cap.restype = ctypes.c_int
@@ -263,6 +266,14 @@ class Topology:
         return _check(load_library().a2a_link_loads_static(
             self._h, src_begin, src_count, _ptr(load), _ptr(dist_sum_total), _ptr(flags), _stream(stream)),
             "a2a_link_loads_static")
+
+    def sssp_loads(self, src_begin: int, src_count: int, iter_sources: int = 64, *, load, dist_sum_total=None,
+                   flags=None, workspace, stream=None) -> int:
+        """a2a_sssp_loads: single-path SSSP baseline, one iteration per ``iter_sources`` sources."""
+        return _check(load_library().a2a_sssp_loads(
+            self._h, src_begin, src_count, iter_sources, _ptr(load), _ptr(dist_sum_total), _ptr(flags),
+            _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream(stream)),
+            "a2a_sssp_loads")
 
     def link_loads_demand(self, src_begin: int, src_count: int, *, demand, load, weighted_dist=None,
                           dist_sum_total=None, flags=None, workspace, stream=None) -> int:

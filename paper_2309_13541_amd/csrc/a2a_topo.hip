@@ -23,6 +23,7 @@
 #include <vector>
 
 #include "a2a_kernels.h"
+#include "a2a_sssp_kernels.h"
 #include "a2a_topo.h"
 
 using namespace a2a_dev;
@@ -42,6 +43,7 @@ struct a2a_topo {
   int32_t* d_out_col = nullptr;
   int32_t* d_in_ptr = nullptr;
   int32_t* d_in_col = nullptr;
+  int32_t* d_in_link = nullptr;  // link id (position in the out-CSR) of every in-CSR entry
   // Read-back slots of a2a_schedule_bound / _cap: kSlots x kSlotWords int64 on the device and in
   // pinned host memory; every call takes the next slot, so calls on different streams or threads
   // do not share one.
@@ -85,7 +87,7 @@ struct Layout {
   int bpb = 0;   // 256-node blocks per batch
   int nb64 = 0;  // 64-node blocks per batch
   int SB = 0;    // super-batches of kSub batches (BFS arrays)
-  bool values = false, loads = false;
+  bool values = false, loads = false, sssp = false;
   size_t Epad = 0;
   size_t off_misc = 0;       // int64 [8]: 0 sigma-inexact flag, 1 dist_sum, 2 reached pairs, 3 DAG links
   size_t off_ltot = 0;       // int64 [G][Lcap]
@@ -100,6 +102,10 @@ struct Layout {
   size_t off_coef = 0;       // double [G][Npad*64]  coef (link loads only)
   size_t off_part = 0;       // double [G][Epad]
   size_t off_wpart = 0;      // double [G][nb64]  demand x distance per (batch, 64-node block)
+  size_t off_cost = 0;       // int64 [G][Npad][64]   single-path baseline: cost, chosen link, paths through
+  size_t off_pick = 0;       // int32 [G][Npad][64]
+  size_t off_sub = 0;        // int32 [G][Npad][64]
+  size_t off_iload = 0;      // uint64 [Epad]
   size_t total = 0;
 };
 
@@ -110,6 +116,7 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
   Layout L;
   L.values = (flags & (A2A_WS_SIGMA | A2A_WS_LOADS)) != 0;
   L.loads = (flags & A2A_WS_LOADS) != 0;
+  L.sssp = (flags & A2A_WS_SSSP) != 0;
   L.Npad = (int)align_up((size_t)t->N, kBlock);
   L.bpb = L.Npad / kBlock;
   L.nb64 = L.Npad / kBfsNodes;
@@ -136,6 +143,10 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
     const size_t o_coef = L.loads ? take((size_t)G * L.Npad * 64 * 8 + 256) : 0;
     const size_t o_part = L.loads ? take((size_t)G * L.Epad * 8) : 0;
     const size_t o_wpart = L.loads ? take((size_t)G * L.nb64 * 8) : 0;
+    const size_t o_cost = L.sssp ? take((size_t)G * L.Npad * 64 * 8) : 0;
+    const size_t o_pick = L.sssp ? take((size_t)G * L.Npad * 64 * 4) : 0;
+    const size_t o_sub = L.sssp ? take((size_t)G * L.Npad * 64 * 4) : 0;
+    const size_t o_iload = L.sssp ? take(L.Epad * 8) : 0;
     if (out) {
       out->off_misc = o_misc;
       out->off_ltot = o_ltot;
@@ -149,6 +160,10 @@ Layout make_layout(const a2a_topo* t, int32_t src_count, int flags, size_t ws_by
       out->off_coef = o_coef;
       out->off_part = o_part;
       out->off_wpart = o_wpart;
+      out->off_cost = o_cost;
+      out->off_pick = o_pick;
+      out->off_sub = o_sub;
+      out->off_iload = o_iload;
       out->total = off;
       out->G = G;
     }
@@ -485,15 +500,20 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
     }
   a2a_topo* t = new (std::nothrow) a2a_topo();
   if (!t) return A2A_ERR_NO_MEMORY;
-  std::vector<int32_t> in_ptr, in_col;
+  std::vector<int32_t> in_ptr, in_col, in_link;
   try {
     in_ptr.assign((size_t)N + 1, 0);
     in_col.resize((size_t)(E > 0 ? E : 1));
+    in_link.resize((size_t)(E > 0 ? E : 1));
     for (int64_t p = 0; p < E; ++p) in_ptr[(size_t)col_idx[p] + 1]++;
     for (int32_t v = 0; v < N; ++v) in_ptr[(size_t)v + 1] += in_ptr[v];
     std::vector<int32_t> fill(in_ptr.begin(), in_ptr.end() - 1);
     for (int32_t u = 0; u < N; ++u)  // ascending link id => in-lists are stable in link order
-      for (int32_t p = row_ptr[u]; p < row_ptr[u + 1]; ++p) in_col[(size_t)fill[col_idx[p]]++] = u;
+      for (int32_t p = row_ptr[u]; p < row_ptr[u + 1]; ++p) {
+        const size_t at = (size_t)fill[col_idx[p]]++;
+        in_col[at] = u;
+        in_link[at] = p;
+      }
     for (int32_t v = 0; v < N; ++v) t->dmax_in = std::max(t->dmax_in, in_ptr[(size_t)v + 1] - in_ptr[v]);
   } catch (const std::bad_alloc&) {
     delete t;
@@ -509,6 +529,7 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
             hipMalloc((void**)&t->d_out_col, cb) == hipSuccess &&
             hipMalloc((void**)&t->d_in_ptr, pb) == hipSuccess &&
             hipMalloc((void**)&t->d_in_col, cb) == hipSuccess &&
+            hipMalloc((void**)&t->d_in_link, cb) == hipSuccess &&
             hipMalloc((void**)&t->d_small, slot_bytes) == hipSuccess &&
             hipHostMalloc((void**)&t->h_pinned, slot_bytes, hipHostMallocDefault) == hipSuccess;
   ok = ok && hipGetSymbolAddress(&t->d_scratch, HIP_SYMBOL(scratch)) == hipSuccess && t->d_scratch != nullptr;
@@ -517,7 +538,8 @@ int a2a_topo_create(int32_t N, const int32_t* row_ptr, const int32_t* col_idx, a
        hipMemcpy(t->d_in_ptr, in_ptr.data(), pb, hipMemcpyHostToDevice) == hipSuccess;
   if (ok && E > 0)
     ok = hipMemcpy(t->d_out_col, col_idx, (size_t)E * 4, hipMemcpyHostToDevice) == hipSuccess &&
-         hipMemcpy(t->d_in_col, in_col.data(), (size_t)E * 4, hipMemcpyHostToDevice) == hipSuccess;
+         hipMemcpy(t->d_in_col, in_col.data(), (size_t)E * 4, hipMemcpyHostToDevice) == hipSuccess &&
+         hipMemcpy(t->d_in_link, in_link.data(), (size_t)E * 4, hipMemcpyHostToDevice) == hipSuccess;
   if (ok && E > 0) ok = probe_depth(t, &t->level_bound) == A2A_OK;
   if (!ok) {
     (void)hipGetLastError();
@@ -538,6 +560,7 @@ void a2a_topo_destroy(a2a_topo* t) {
   if (t->d_out_col) (void)hipFree(t->d_out_col);
   if (t->d_in_ptr) (void)hipFree(t->d_in_ptr);
   if (t->d_in_col) (void)hipFree(t->d_in_col);
+  if (t->d_in_link) (void)hipFree(t->d_in_link);
   if (t->d_small) (void)hipFree(t->d_small);
   if (t->h_pinned) (void)hipHostFree(t->h_pinned);
   delete t;
@@ -553,7 +576,7 @@ int a2a_topo_info(const a2a_topo* t, int32_t* N, int64_t* E, int32_t* dmax, int3
 }
 
 size_t a2a_workspace_bytes(const a2a_topo* t, int32_t src_count, int flags) {
-  if (!t || src_count < 0 || src_count > t->N) return 0;
+  if (!t || src_count < 0 || (size_t)src_count > align_up((size_t)t->N, 64)) return 0;
   if (src_count == 0) return 256;
   const Layout L = make_layout(t, src_count, flags & 0xff, 0, true, (flags & A2A_WS_MINIMAL) != 0);
   return L.total;
@@ -711,6 +734,59 @@ int a2a_link_loads_demand(const a2a_topo* t, int32_t src_begin, int32_t src_coun
   if (!demand) return A2A_ERR_INVALID_ARG;
   return link_loads(t, src_begin, src_count, demand, load, weighted_dist, dist_sum_total, flags, workspace,
                     workspace_bytes, hip_stream);
+}
+
+int a2a_sssp_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32_t iter_sources, double* load,
+                   int64_t* dist_sum_total, int64_t* flags, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+  int rc = check_common(t, src_begin, src_count, workspace);
+  if (rc != A2A_OK) return rc;
+  if (!load && t->E > 0) return A2A_ERR_INVALID_ARG;
+  if (iter_sources <= 0 || iter_sources % 64 != 0) return A2A_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (src_count == 0) {
+    if (t->E > 0) HIP_TRY(zero_async(load, (size_t)t->E * 8, st));
+    if (dist_sum_total) HIP_TRY(zero_async(dist_sum_total, 8, st));
+    if (flags) HIP_TRY(zero_async(flags, 8, st));
+    return A2A_OK;
+  }
+  // one iteration = one group: the workspace has to hold all its batches
+  const int nb = (src_count + 63) / 64;
+  const int per_iter = std::min(iter_sources / 64, nb);
+  Run r;
+  r.t = t;
+  r.L = make_layout(t, per_iter * 64, A2A_WS_SSSP, workspace_bytes, false, false);
+  if (r.L.G < per_iter) return A2A_ERR_WORKSPACE_TOO_SMALL;
+  r.ws = (char*)workspace;
+  r.st = st;
+  r.src_begin = src_begin;
+  r.src_count = src_count;
+  const Layout& L = r.L;
+  SsspView sv;
+  sv.cost = (long long*)(r.ws + L.off_cost);
+  sv.pick = (int*)(r.ws + L.off_pick);
+  sv.sub = (int*)(r.ws + L.off_sub);
+  sv.iload = (unsigned long long*)(r.ws + L.off_iload);
+  HIP_TRY(zero_async(r.misc(), 64, st));
+  HIP_TRY(zero_async(sv.iload, L.Epad * 8, st));
+  const int depth = t->level_bound;
+  for (int b0 = 0; b0 < nb; b0 += per_iter) {
+    const GroupView gv = r.view(b0, nb - b0 < per_iter ? nb - b0 : per_iter);
+    rc = run_bfs(r, gv, depth);
+    if (rc != A2A_OK) return rc;
+    const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
+    for (int l = 1; l <= depth; ++l)
+      k_sssp_fwd<<<grid, kBlock, 0, st>>>(t->d_in_ptr, t->d_in_col, t->d_in_link, gv, sv, l);
+    for (int l = depth; l >= 0; --l) k_sssp_bwd<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, sv, l);
+    rc = run_fold(r, gv, depth);
+    if (rc != A2A_OK) return rc;
+  }
+  if (t->E > 0)
+    k_sssp_output<<<(unsigned)((t->E + kBlock - 1) / kBlock), kBlock, 0, st>>>(sv.iload, (long long)t->E, load);
+  k_finish<<<1, 64, 0, st>>>(r.misc(), (long long)src_count * (t->N - 1), (long long*)dist_sum_total,
+                             nullptr, (long long*)flags);
+  HIP_TRY(hipGetLastError());
+  return A2A_OK;
 }
 
 int a2a_schedule_bound(const a2a_topo* t, const double* load, int64_t sum_dist, int64_t flags,
