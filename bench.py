@@ -122,6 +122,9 @@ def main():
                     help="skip the a2a_distances leg (distance matrix only, reported beside the metric)")
     ap.add_argument("--no-demand", action="store_true",
                     help="skip the a2a_link_loads_demand leg (unequal demands, reported beside the metric)")
+    ap.add_argument("--no-sssp", action="store_true",
+                    help="skip the a2a_sssp_loads leg (single-path SSSP baseline, reported beside the metric)")
+    ap.add_argument("--sssp-iter-sources", type=int, default=512)
     ap.add_argument("--max-workspace-gib", type=float, default=None)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="kept for old command lines: the 1 GiB device copies (known bytes, for scaling "
@@ -259,6 +262,41 @@ def main():
         assert wd > 0 and abs(total / wd - 1.0) < 1e-9, (total, wd)
         del dem, dload
 
+    # single-path SSSP baseline over all sources, reported beside the metric
+    sssp_leg = None
+    if not args.no_sssp:
+        k = max(64, args.sssp_iter_sources // 64 * 64)
+        wss = torch.empty(topo.workspace_bytes(min(k, (N + 63) // 64 * 64), a2a.WS_SSSP), dtype=torch.uint8, device="cuda")
+        sload = torch.empty(E, dtype=torch.float64, device="cuda")
+        sdsum = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+        def sstep():
+            topo.sssp_loads(0, N, k, load=sload, dist_sum_total=sdsum, workspace=wss)
+
+        sstep()
+        torch.cuda.synchronize()
+        n_s = max(1, min(args.steps, 3))
+        t0 = time.perf_counter()
+        for _ in range(n_s):
+            sstep()
+        torch.cuda.synchronize()
+        ssec = (time.perf_counter() - t0) / n_s
+        total = float(sload.sum().item())
+        assert total == float(sdsum.item()) == float(sum_dist), (total, sum_dist)  # one path of D links per pair
+        sssp_leg = {"ms_per_step": ssec * 1e3, "teps": N * E / ssec, "unit": "edges/s", "iter_sources": k,
+                    "max_load": float(sload.max().item()), "max_load_over_ewsp": float(sload.max().item()) / bound.max_load,
+                    "what": "a2a_sssp_loads over all sources: BFS + cost recursion + path counts per iteration"}
+        if not args.no_cpu:
+            import oracle
+            oracle.build(force=False)
+            n_or = min(N, 2 * k)
+            t0 = time.perf_counter()
+            oracle.sssp(rp, col, 0, n_or, iter_sources=k)
+            t_or = time.perf_counter() - t0
+            sssp_leg["cpu_oracle"] = {"value": n_or * E / t_or, "unit": "edges/s", "cores": 1, "seconds": t_or,
+                                      "sample": f"sources 0..{n_or - 1} of {N} (serial by definition)"}
+        del wss, sload
+
     # a2a_distances alone (BFS + the int32 distance matrix), reported beside the metric
     dist_leg = None
     ws_gib = ws.numel() / 2 ** 30
@@ -337,6 +375,7 @@ def main():
         "roofline": roofline,
         "distances": dist_leg,
         "demand": dem_leg,
+        "sssp": sssp_leg,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
