@@ -497,6 +497,25 @@ __device__ __forceinline__ Tile tile_request_idx(const NodeIdx* __restrict__ lev
   return t;
 }
 
+// Sparse levels: most of a wave's 64 nodes have no source on the level, and a tile of eight nodes costs
+// the same with one node on it as with eight.  This moves the per-node values of the nodes in `active`
+// to the lowest lanes (in node order; the others follow behind them) and returns their number, so that
+// the tiles are filled from the front and only ceil(count / 8) of them are visited.  nid: the node's id.
+__device__ __forceinline__ int compact_nodes(uint64_t active, int lane, NodeIdx& me, LinkRange& lr, int& nid) {
+  const int count = __popcll(active);
+  if (count == kWave) return count;
+  const int r = (int)rank_in(active);
+  const int dst = 4 * (((active >> lane) & 1ull) ? r : count + lane - r);  // a permutation of the lanes
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_permute(dst, (int)(uint32_t)me.mask);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_permute(dst, (int)(uint32_t)(me.mask >> 32));
+  me.mask = ((uint64_t)hi << 32) | lo;
+  me.off = (uint32_t)__builtin_amdgcn_ds_permute(dst, (int)me.off);
+  lr.p0 = __builtin_amdgcn_ds_permute(dst, lr.p0);
+  lr.p1 = __builtin_amdgcn_ds_permute(dst, lr.p1);
+  nid = __builtin_amdgcn_ds_permute(dst, nid);
+  return count;
+}
+
 // Issues the (up to) eight row gathers of node i of the current tile: lanes in mk & want read
 // their entry of the link's row.  Returns the number of (source, link) pairs.
 template <typename T>
@@ -1006,7 +1025,7 @@ fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, 
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
   TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  const NodeIdx me = load_idx(cur + v0 + lane);
+  NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
   LinkRange lr;
@@ -1015,16 +1034,18 @@ fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, 
     lr.p0 = in_ptr[v0 + lane];
     lr.p1 = in_ptr[v0 + lane + 1];
   }
+  int nid = v0 + lane;
+  const int tiles = (compact_nodes(nodes_active, lane, me, lr, nid) + 7) >> 3;
   bool inexact = false;
   int dag = 0;
   int q;
   Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
-  int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
+  int nb_next = tiles > 1 ? tile_request_col(in_col, lr, 1, 0, lane, q) : -1;
 #pragma unroll 1
-  for (int c = 0; c < 8; ++c) {
-    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
-    nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
-    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+  for (int c = 0; c < tiles; ++c) {
+    const Tile tile_next = tile_request_idx(prev, c + 1 < tiles ? nb_next : -1);
+    nb_next = c + 2 < tiles ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+    {
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
@@ -1354,7 +1375,7 @@ bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
   double wd = 0.0;
-  const NodeIdx me = load_idx(cur + u0 + lane);
+  NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
   LinkRange lr;
@@ -1363,20 +1384,23 @@ bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col
     lr.p0 = out_ptr[u0 + lane];
     lr.p1 = out_ptr[u0 + lane + 1];
   }
-  int q, q_next, q_nn;
+  int nid = u0 + lane;
+  const int tiles = (compact_nodes(nodes_active, lane, me, lr, nid) + 7) >> 3;
+  int q, q_next = -1, q_nn;
   Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
-  int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
+  int nb_next = tiles > 1 ? tile_request_col(out_col, lr, 1, 0, lane, q_next) : -1;
 #pragma unroll 1
-  for (int c = 0; c < 8; ++c) {
-    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+  for (int c = 0; c < tiles; ++c) {
+    const Tile tile_next = tile_request_idx(next, c + 1 < tiles ? nb_next : -1);
     nb_next = -1;
     q_nn = -1;
-    if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
-    if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
+    if (c + 2 < tiles) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    {
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
-      const double* __restrict__ dem_row = kDemand ? dem + (size_t)(u0 + node) * (size_t)gv.dem_ld : nullptr;
+      const double* __restrict__ dem_row =
+          kDemand ? dem + (size_t)__shfl(nid, node, kWave) * (size_t)gv.dem_ld : nullptr;
       const double tot = kSlots ? slot_bwd(dat, cf, tile, mu, ofu, false, lane, dem_row, wd)
                                 : few_bwd(dat, cf, tile, mu, ofu, false, lane, dem_row, wd);
       if (q >= 0 && (tile.mask & mu) != 0) unsafeAtomicAdd(&pt[q], tot);
