@@ -105,8 +105,14 @@ def copy_bandwidth(torch, reps=5):
     end.record()
     torch.cuda.synchronize()
     ms = beg.elapsed_time(end) / reps
+    beg.record()
+    for _ in range(reps):
+        dst.zero_()
+    end.record()
+    torch.cuda.synchronize()
+    fill_ms = beg.elapsed_time(end) / reps
     del src, dst
-    return 2.0 * 2 ** 30 / (ms * 1e-3) / 1e9
+    return 2.0 * 2 ** 30 / (ms * 1e-3) / 1e9, 2 ** 30 / (fill_ms * 1e-3) / 1e9
 
 
 def main():
@@ -125,6 +131,9 @@ def main():
     ap.add_argument("--no-sssp", action="store_true",
                     help="skip the a2a_sssp_loads leg (single-path SSSP baseline, reported beside the metric)")
     ap.add_argument("--sssp-iter-sources", type=int, default=512)
+    ap.add_argument("--graph", action="store_true",
+                    help="record a2a_link_loads into a HIP graph once and replay it in every step (the call only "
+                         "enqueues kernels; small topologies are bound by launches, which a replay makes cheaper)")
     ap.add_argument("--max-workspace-gib", type=float, default=None)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="kept for old command lines: the 1 GiB device copies (known bytes, for scaling "
@@ -153,12 +162,25 @@ def main():
     dsum = torch.zeros(1, dtype=torch.int64, device="cuda")
     flags = torch.zeros(1, dtype=torch.int64, device="cuda")
 
+    graph = None
+
     def step():
-        topo.link_loads(0, N, load=load, dist_sum_total=dsum, flags=flags, workspace=ws)
+        if graph is not None:
+            graph.replay()
+        else:
+            topo.link_loads(0, N, load=load, dist_sum_total=dsum, flags=flags, workspace=ws)
         # sum_dist / flags stay on the device until the end; the bound needs Lmax only
         return topo.schedule_bound(load, 0, 0, 1.0, 1.0)[0]
 
-    copy_gbps = copy_bandwidth(torch)
+    if args.graph:
+        step()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            topo.link_loads(0, N, load=load, dist_sum_total=dsum, flags=flags, workspace=ws)
+        graph = g
+
+    copy_gbps, fill_gbps = copy_bandwidth(torch)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -176,6 +198,7 @@ def main():
     load_timed = load.clone()
     # untimed: per-kernel split from HIP events around every launch, on the stream the kernels run on
     prof_steps = 2
+    graph = None  # the profiled steps are launched one by one
     topo.profile_enable(1)
     for _ in range(prof_steps):
         step()
@@ -226,7 +249,7 @@ def main():
         "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
         "alg_bytes_per_launch": k_alg * steps / n_l, "avg_launch_ms": g_ms[kname] / n_l,
         "launches_per_step": n_l / steps,
-        "copy_GBps": copy_gbps, "frac_of_copy": achieved / copy_gbps,
+        "copy_GBps": copy_gbps, "fill_GBps": fill_gbps, "frac_of_copy": achieved / copy_gbps,
         "whole_path": {"alg_bytes": alg_total, "GBps": alg_total / sec / 1e9,
                        "frac": alg_total / sec / 1e9 / HBM_PEAK_GBPS,
                        "frac_of_copy": alg_total / sec / 1e9 / copy_gbps,
@@ -367,7 +390,7 @@ def main():
             "C1": "8x8 torus", "C2": "hypercube n=10", "C3": "16x16x16 torus",
             "C4": "Imase-Itoh N=16384 d=4", "C5": "random 8-regular digraph N=65536 seed 1234",
         }[args.config] + ", unit all-pairs demand", "N": N, "E": E, "sources": N,
-            "workspace_GiB": ws_gib, "groups_per_step": prof["groups"] // max(prof["calls"], 1),
+            "launch": "graph replay" if args.graph else "eager", "workspace_GiB": ws_gib, "groups_per_step": prof["groups"] // max(prof["calls"], 1),
             "depth": prof["depth"], "dag_links": dag},
         "result": {"sum_dist": sum_dist, "max_load": bound.max_load, "argmax_arc": bound.argmax_arc,
                    "rerun_bitwise": rerun_bitwise, "ratio_to_lower_bound": bound.ratio, "flags": fl},

@@ -240,9 +240,12 @@ __device__ __forceinline__ uint64_t valid_mask(int src_count, int batch) {
 // The BFS works on super-batches of kSub batches: the masks of one node for the kSub batches
 // lie next to each other (64 bytes), so that the kSub lanes that look at the same in-neighbour
 // share one memory request.
-constexpr int kSub = 8;
-constexpr int kBfsBlock = 512;                   // threads: kBfsNodes nodes x kSub batches
-constexpr int kBfsNodes = kBfsBlock / kSub;      // 64 nodes per BFS workgroup
+#ifndef A2A_KSUB
+#define A2A_KSUB 8
+#endif
+constexpr int kSub = A2A_KSUB;
+constexpr int kBfsNodes = 64;                    // nodes per BFS workgroup
+constexpr int kBfsBlock = kBfsNodes * kSub;      // threads: kBfsNodes nodes x kSub batches
 constexpr int kBfsWaves = kBfsBlock / kWave;
 
 // Everything a level kernel needs to find its batch's arrays.  G batches; SB = ceil(G/kSub)
@@ -377,9 +380,8 @@ k_bfs_level(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_c
   if (t < kSub) s_cnt[t] = 0;
   __syncthreads();
   int pc = __popcll(nw);
-  pc += __shfl_xor(pc, 8, kWave);
-  pc += __shfl_xor(pc, 16, kWave);
-  pc += __shfl_xor(pc, 32, kWave);
+#pragma unroll
+  for (int o = kSub; o < kWave; o <<= 1) pc += __shfl_xor(pc, o, kWave);
   if (lane_id() < kSub && pc != 0) atomicAdd(&s_cnt[k], pc);
   __syncthreads();
   if (t < kSub) {
@@ -429,12 +431,11 @@ __global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int d
     } else {
       const int c = __popcll(m);
       int x = c;  // inclusive prefix over the wave's nodes, per batch
-      int y = __shfl_up(x, 8, kWave);
-      if (lane >= 8) x += y;
-      y = __shfl_up(x, 16, kWave);
-      if (lane >= 16) x += y;
-      y = __shfl_up(x, 32, kWave);
-      if (lane >= 32) x += y;
+#pragma unroll
+      for (int o = kSub; o < kWave; o <<= 1) {
+        const int y = __shfl_up(x, o, kWave);
+        if (lane >= o) x += y;
+      }
       if (lane >= kWave - kSub) s_w[wid][k] = x;
       __syncthreads();
       int base = g < gv.G ? gv.bsum[((size_t)g * gv.Lcap + l) * gv.nb64 + nblk] : 0;
