@@ -1,11 +1,17 @@
 """Benchmark: all-pairs BFS + EwSP link loads on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--cpu-sources S]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--cpu-sources S] [--graph]
 
 One step = one pass of the whole hot path over the topology: a2a_link_loads over all N
 sources (bit-parallel BFS, forward path counts, backward dependency pass, ordered reduction)
 followed by a2a_schedule_bound.  The CSR is resident on the device before the timed region.
 Prints one JSON line.  TEPS = N * E / seconds (one traversed edge = one (source, link) pair).
+
+The timed region holds the K steps and nothing else.  The per-kernel split (HIP events around every
+launch, on the stream the kernels run on) comes from two further, untimed steps; one more untimed
+step counts the (source, link) pairs on shortest paths for the algorithmic bytes.  Beside the metric:
+a plain 1 GiB device copy and fill (what this machine's HBM gives a streaming kernel), a2a_distances,
+a2a_link_loads_demand, a2a_sssp_loads, and the CPU oracle on a bounded sample (all cores and one core).
 """
 import argparse
 import json
