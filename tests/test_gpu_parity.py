@@ -145,6 +145,51 @@ def test_small_graphs_everything(a2a, oracle, name):
     topo.close()
 
 
+def random_digraph(seed):
+    """A seeded digraph of no particular shape: 1 to 330 nodes, out-degrees from 0 to 12 drawn per node (so
+    in-degrees vary as well, some nodes have none), parallel links left in, self-loops dropped; one in four
+    graphs gets a few nodes without any links."""
+    rng = np.random.default_rng(seed)
+    N = int(rng.integers(1, 331))
+    dmax = int(rng.integers(1, 13))
+    rows = []
+    for u in range(N):
+        deg = int(rng.integers(1 if seed % 2 else 0, dmax + 1))  # odd seeds: every node has an out-link
+        rows.append([int(w) for w in rng.integers(0, N, size=deg) if int(w) != u])
+    if seed % 4 == 0:
+        for u in rng.integers(0, N, size=min(N, 5)):
+            rows[int(u)] = []
+    return gen.csr_from_rows(rows)
+
+
+@pytest.mark.parametrize("block", range(8))
+def test_random_digraphs_everything(a2a, oracle, block):
+    """160 seeded random digraphs (20 per case): distances, path counts, sums, flags and link loads against the
+    oracle, all sources and one partial source range each."""
+    for seed in range(20 * block, 20 * block + 20):
+        rp, col = random_digraph(seed)
+        N = len(rp) - 1
+        print(f"seed {seed} N={N} E={len(col)}", flush=True)
+        o = oracle.run(rp, col, want_dist=True, want_sigma=True)
+        topo = a2a.Topology(rp, col)
+        dist, sigma, dsum, unr, flags = run_distances(topo)
+        assert np.array_equal(dist, o.dist) and np.array_equal(dsum, o.dist_sum), seed
+        assert unr == o.unreachable and flags == o.flags, seed
+        if not (o.flags & 1):
+            assert_sigma_equal(sigma, o.sigma)
+        load, dtot, lflags = run_link_loads(topo)
+        assert dtot == int(o.dist_sum.sum()) and lflags == o.flags, seed
+        if len(col):
+            assert_loads_close(load, o.load)
+            s0 = seed % N
+            cnt = min(N - s0, 1 + seed % 97)
+            part = oracle.run(rp, col, s0, cnt)
+            pl, pd, pf = run_link_loads(topo, s0, cnt)
+            assert pd == int(part.dist_sum.sum()), seed
+            assert_loads_close(pl, part.load)
+        topo.close()
+
+
 @pytest.mark.parametrize("name", sorted(FUNNELS))
 def test_funnels_precision_boundary(a2a, oracle, name):
     """Graphs whose levels 3..10 (for sources 0..63) are as full as chosen, with the change from single- to
