@@ -255,7 +255,6 @@ struct Run {
     return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] > 0.0 &&
            lanes_per_node[level] < kNominalRows;
   }
-  bool rows(int level) const { return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] >= kNominalRows; }
   // Path counts on `level` are at most (largest in-degree)^level: while that is below 2^24 the level
   // keeps sigma in single precision (exact: whole numbers a float holds), which halves what the
   // forward pass writes and gathers and what the backward pass reads of it.  If a level is narrow,
