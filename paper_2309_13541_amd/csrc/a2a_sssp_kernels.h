@@ -52,18 +52,31 @@ k_sssp_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_co
     long long best = 0x7fffffffffffffffll;
     int via = -1;
     const int p1 = in_ptr[v + 1];
-    for (int p = in_ptr[v]; p < p1; ++p) {
-      const int u = in_col[p];
-      const uint64_t m = mv & level_mask(gv, g, level - 1, u);
-      if (m == 0) continue;
-      const int a = in_link[p];
-      const long long w = (long long)sv.iload[a];
-      if ((m >> lane) & 1ull) {
+    for (int p = in_ptr[v]; p < p1; p += 8) {  // eight in-links at a time, all requests issued before any is used
+      int u[8], a[8];
+      uint64_t m[8];
+      long long w[8], c[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        u[j] = p + j < p1 ? in_col[p + j] : -1;
+        a[j] = p + j < p1 ? in_link[p + j] : 0;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m[j] = u[j] >= 0 ? mv & level_mask(gv, g, level - 1, u[j]) : 0ull;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        w[j] = m[j] != 0 ? (long long)sv.iload[a[j]] : 0ll;
         // the level before level 1 holds the sources themselves: cost 0, no row
-        const long long c = (level == 1 ? 0ll : sv.cost[rows + (size_t)u * 64 + lane]) + w;
-        if (c < best) {
-          best = c;
-          via = a;
+        c[j] = (level > 1 && ((m[j] >> lane) & 1ull)) ? sv.cost[rows + (size_t)u[j] * 64 + lane] : 0ll;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {  // ascending link id: the strict comparison keeps the lowest among equals
+        if ((m[j] >> lane) & 1ull) {
+          const long long t = c[j] + w[j];
+          if (t < best) {
+            best = t;
+            via = a[j];
+          }
         }
       }
     }
@@ -99,15 +112,35 @@ k_sssp_bwd(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_
     int through = 1;  // the pair's own commodity (not counted at the source itself, level 0: never read)
     if (deeper) {
       const int q1 = out_ptr[u + 1];
-      for (int q = out_ptr[u]; q < q1; ++q) {
-        const int w = out_col[q];
-        const uint64_t m = mu & level_mask(gv, g, level + 1, w);
-        if (m == 0) continue;
-        int x = 0;
-        if (((m >> lane) & 1ull) && sv.pick[rows + (size_t)w * 64 + lane] == q) x = sv.sub[rows + (size_t)w * 64 + lane];
-        through += x;
-        const int tot = wave_sum_int(x);
-        if (lane == 0 && tot != 0) atomicAdd(&sv.iload[q], (unsigned long long)tot);
+      for (int q = out_ptr[u]; q < q1; q += 8) {  // eight out-links at a time
+        int w[8], pk[8], x[8];
+        uint64_t m[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[j] = q + j < q1 ? out_col[q + j] : -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m[j] = w[j] >= 0 ? mu & level_mask(gv, g, level + 1, w[j]) : 0ull;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bool on = (m[j] >> lane) & 1ull;
+          pk[j] = on ? sv.pick[rows + (size_t)w[j] * 64 + lane] : -1;
+          x[j] = on ? sv.sub[rows + (size_t)w[j] * 64 + lane] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          if (pk[j] != q + j) x[j] = 0;
+          through += x[j];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] += __shfl_xor(x[j], o, kWave);
+        }
+        // lane j adds the total of link q + j
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (lane == j) mine = x[j];
+        if (lane < 8 && mine != 0) atomicAdd(&sv.iload[q + lane], (unsigned long long)mine);
       }
     }
     if (level > 0 && ((mu >> lane) & 1ull)) sv.sub[rows + (size_t)u * 64 + lane] = through;
