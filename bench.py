@@ -250,11 +250,28 @@ def main():
     alg_total = sum(alg.values())
     lay_total = layout_bytes(prof, dag_level, nb, E, steps, prof["narrow_levels"])
     traffic = read_traffic(cfg, kname)
+    # the single longest launch of that kernel (one BFS level), with its own bytes
+    longest = None
+    for c in groups[kname]:
+        for l, x in enumerate(prof[c]["ms_level"]):
+            if x > 0 and (longest is None or x > longest[2]):
+                longest = (c, l, x)
+    longest_launch = None
+    if longest is not None and kname in ("k_fwd", "k_bwd"):
+        c, l, x = longest
+        one = {k: dict(v, ms_level=[m if (k == c and i == l) else 0.0 for i, m in enumerate(v["ms_level"])])
+               if isinstance(v, dict) and "ms_level" in v else v for k, v in prof.items()}
+        a_one = algorithmic_bytes(one, dag_level, nb, E, steps)[c]
+        ms_one = x / steps
+        longest_launch = {"kernel": f"{kname} level {l} ({c.split('_')[1]})", "ms": ms_one, "alg_bytes": a_one,
+                          "achieved": a_one / (ms_one * 1e-3) / 1e9, "frac": a_one / (ms_one * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          "traffic": read_traffic(cfg, f"{kname}[level {l}]")}
     roofline = {
         "bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
         "alg_bytes_per_launch": k_alg * steps / n_l, "avg_launch_ms": g_ms[kname] / n_l,
         "launches_per_step": n_l / steps,
+        "longest_launch": longest_launch,
         "copy_GBps": copy_gbps, "fill_GBps": fill_gbps, "frac_of_copy": achieved / copy_gbps,
         "whole_path": {"alg_bytes": alg_total, "GBps": alg_total / sec / 1e9,
                        "frac": alg_total / sec / 1e9 / HBM_PEAK_GBPS,
