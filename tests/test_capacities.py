@@ -42,6 +42,14 @@ def test_bottlenecked_testbed_value(oracle):
     got = oracle.bound_cap(rp, r.load, cap, int(r.dist_sum.sum()), m=1.0, b=float(pv["upper_bound_b_GBps"]))
     assert got["flow_value"] == pytest.approx(float(frac(pv["upper_bound_f"])), rel=1e-12)
     assert math.floor(got["throughput_upper"] * 100) / 100 == float(pv["upper_bound_GBps"])
+    # The same without assuming that the six links share the limit evenly.  The schedule of Sec. 5.1 is a
+    # link-based one (Sec. 2.2): forwarded traffic passes through the host too, so everything a host's links
+    # send, 54 link-units per unit of flow here, has to fit the host's 100 Gbps = 4 links' worth:
+    # f = min(1 / largest link load, 4 / largest egress of a host).
+    egress = np.add.reduceat(r.load, rp[:-1])
+    f = min(1.0 / r.load.max(), (100.0 / 25.0) / egress.max())
+    assert egress.max() == pytest.approx(54.0, rel=1e-12)
+    assert f == pytest.approx(float(frac(pv["upper_bound_f"])), rel=1e-12)
 
 
 def test_links_twice_as_fast_halve_the_time(oracle):
