@@ -34,15 +34,16 @@ __device__ __forceinline__ uint64_t level_mask(const GroupView& gv, int g, int l
 // so the strict comparison keeps the lowest id among equals.
 __global__ void __launch_bounds__(kBlock)
 k_sssp_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col,
-           const int32_t* __restrict__ in_link, GroupView gv, SsspView sv, int level) {
+           const int32_t* __restrict__ in_link, GroupView gv, SsspView sv, int level, int npw) {
   int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  if (!map_block(gv.G, gv.bpb * (kWave / npw), gv.inflight, g, nblk)) return;
   if (gv.ltot[(size_t)g * gv.Lcap + level] == 0) return;
   const int lane = lane_id();
-  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  // a wave takes npw consecutive nodes (64, or fewer when an iteration has too few batches to fill the chip)
+  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * npw);
   if (v0 >= gv.N) return;
   const size_t rows = (size_t)g * gv.Npad * 64;
-  const uint64_t mine = v0 + lane < gv.N ? level_mask(gv, g, level, v0 + lane) : 0ull;
+  const uint64_t mine = (lane < npw && v0 + lane < gv.N) ? level_mask(gv, g, level, v0 + lane) : 0ull;
   uint64_t todo = __ballot(mine != 0);
   while (todo) {
     const int i = __builtin_ctzll(todo);
@@ -92,17 +93,17 @@ k_sssp_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_co
 // next one starts after this kernel's last launch.
 __global__ void __launch_bounds__(kBlock)
 k_sssp_bwd(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, SsspView sv,
-           int level) {
+           int level, int npw) {
   int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
+  if (!map_block(gv.G, gv.bpb * (kWave / npw), gv.inflight, g, nblk)) return;
   const long long* __restrict__ lt = gv.ltot + (size_t)g * gv.Lcap;
   if (lt[level] == 0) return;
   const bool deeper = level + 1 < gv.Lcap && lt[level + 1] != 0;
   const int lane = lane_id();
-  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
+  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * npw);
   if (u0 >= gv.N) return;
   const size_t rows = (size_t)g * gv.Npad * 64;
-  const uint64_t mine = u0 + lane < gv.N ? level_mask(gv, g, level, u0 + lane) : 0ull;
+  const uint64_t mine = (lane < npw && u0 + lane < gv.N) ? level_mask(gv, g, level, u0 + lane) : 0ull;
   uint64_t todo = __ballot(mine != 0);
   while (todo) {
     const int i = __builtin_ctzll(todo);

@@ -773,10 +773,13 @@ int a2a_sssp_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, int3
     const GroupView gv = r.view(b0, nb - b0 < per_iter ? nb - b0 : per_iter);
     rc = run_bfs(r, gv, depth);
     if (rc != A2A_OK) return rc;
-    const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
+    // nodes per wave: 64, or 8 when the iteration has too few batches to give every SIMD a wave otherwise
+    const int npw = (long long)gv.G * L.Npad >= 64ll * 4096 ? 64 : 8;
+    const unsigned grid = grid_for(gv.G, L.bpb * (kWave / npw), r.inflight);
     for (int l = 1; l <= depth; ++l)
-      k_sssp_fwd<<<grid, kBlock, 0, st>>>(t->d_in_ptr, t->d_in_col, t->d_in_link, gv, sv, l);
-    for (int l = depth; l >= 0; --l) k_sssp_bwd<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, sv, l);
+      k_sssp_fwd<<<grid, kBlock, 0, st>>>(t->d_in_ptr, t->d_in_col, t->d_in_link, gv, sv, l, npw);
+    for (int l = depth; l >= 0; --l)
+      k_sssp_bwd<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, sv, l, npw);
     rc = run_fold(r, gv, depth);
     if (rc != A2A_OK) return rc;
   }
