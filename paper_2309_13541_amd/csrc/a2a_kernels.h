@@ -537,13 +537,37 @@ __device__ __forceinline__ int gather8(const T* __restrict__ rows, const Tile& t
   return pairs;
 }
 
+// The rows of the (up to eight) nodes of a tile are adjacent in a batch's level-compact array:
+// entries of0 .. end - 1, of0 = where the first of the tile's nodes that is on the level starts.
+struct TileSpan {
+  uint32_t of0, end;
+};
+__device__ __forceinline__ TileSpan tile_span(const NodeIdx& me, uint64_t nodes_active, int c) {
+  const uint32_t on = (uint32_t)(nodes_active >> (8 * c)) & 0xffu;  // not 0
+  const int first = 8 * c + __builtin_ctz(on), last = 8 * c + 31 - __builtin_clz(on);
+  TileSpan t;
+  t.of0 = (uint32_t)__builtin_amdgcn_readlane((int)me.off, first);
+  t.end = (uint32_t)__builtin_amdgcn_readlane((int)me.off, last) + (uint32_t)__popcll(readlane64(me.mask, last));
+  return t;
+}
+
+// The span's entries from their copy in LDS (stage[0] = entry of0), 64 at a time; every store but the
+// first starts on a 128-byte boundary of the array, so whole lines go out.
+template <typename T>
+__device__ __forceinline__ void store_staged(T* __restrict__ arr, const T* __restrict__ stage, TileSpan t, int lane) {
+  constexpr uint32_t kPerLine = 128 / sizeof(T);
+  for (int k = lane - (int)(t.of0 & (kPerLine - 1)); (int)t.of0 + k < (int)t.end; k += kWave)
+    if (k >= 0) entry(arr, t.of0 + (uint32_t)k) = stage[k];
+}
+
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
 // cf (may be null): the deepest level's coef is just 1/sigma, which goes there now.
 // The gathered values are widened here, where they are used, so that the requests stay in
-// flight until then.
+// flight until then.  sigma goes to `stage`, the LDS copy of the tile's piece of the sigma array
+// (stage[0] = entry of0), which the caller stores when the tile is done.
 template <typename TIn, typename TOut>
-__device__ __forceinline__ bool fwd_finish(TOut* __restrict__ out, double* __restrict__ cf, const NodeIdx& me, int node,
-                                           const TIn (&x)[8]) {
+__device__ __forceinline__ bool fwd_finish(TOut* __restrict__ stage, uint32_t of0, double* __restrict__ cf,
+                                           const NodeIdx& me, int node, const TIn (&x)[8]) {
   double a = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) a += (double)hold(x[j]);
@@ -552,7 +576,7 @@ __device__ __forceinline__ bool fwd_finish(TOut* __restrict__ out, double* __res
   bool big = false;
   if (lane_in(newv)) {
     const uint32_t e = of + rank_in(newv);
-    entry(out, e) = (TOut)a;
+    stage[e - of0] = (TOut)a;
     if (cf != nullptr) entry(cf, e) = recip(a);
     big = a >= kTwo53;
   }
@@ -563,7 +587,7 @@ __device__ __forceinline__ bool fwd_finish(TOut* __restrict__ out, double* __res
 template <bool kCountDag, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv,
-         int level, bool init_coef, long long* __restrict__ misc, int g, int v0) {
+         int level, bool init_coef, long long* __restrict__ misc, int g, int v0, TOut* __restrict__ stage) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
@@ -591,16 +615,17 @@ fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col,
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       TIn xa[8], xb[8];
       uint64_t m[8];
+      const TileSpan span = tile_span(me, nodes_active, c);
       int pairs = gather8(rows, tile, 0, readlane64(me.mask, 8 * c), xa, m);
 #pragma unroll 1
       for (int i = 0; i < 8; i += 2) {  // two nodes per round, the next one's rows always in flight
         pairs += gather8(rows, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, m);
-        inexact |= fwd_finish(out, cf, me, 8 * c + i, xa);
+        inexact |= fwd_finish(stage, span.of0, cf, me, 8 * c + i, xa);
         if (i + 2 < 8) pairs += gather8(rows, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, m);
-        inexact |= fwd_finish(out, cf, me, 8 * c + i + 1, xb);
+        inexact |= fwd_finish(stage, span.of0, cf, me, 8 * c + i + 1, xb);
       }
       if (kCountDag) dag += pairs;
-      // nodes with more than eight in-links: add the rest to the stored entries
+      // nodes with more than eight in-links: add the rest to the staged entries
       const int p0 = __shfl(lr.p0, 8 * c + (lane >> 3), kWave), p1 = __shfl(lr.p1, 8 * c + (lane >> 3), kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
@@ -616,13 +641,16 @@ fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col,
           const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
           if (lane_in(newv)) {
             const uint32_t pos = of + rank_in(newv);
-            a += (double)entry(out, pos);
-            entry(out, pos) = (TOut)a;
+            a += (double)stage[pos - span.of0];  // written by this lane
+            stage[pos - span.of0] = (TOut)a;
             if (cf != nullptr) entry(cf, pos) = recip(a);
             inexact |= a >= kTwo53;
           }
         }
       }
+      __builtin_amdgcn_wave_barrier();
+      store_staged(out, stage, span, lane);
+      __builtin_amdgcn_wave_barrier();
     }
     tile = tile_next;
   }
@@ -1052,7 +1080,7 @@ fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, 
       const uint32_t ofu = (uint32_t)__shfl((int)me.off, node, kWave);
       inexact |= kSlots ? slot_fwd(rows, out, cf, tile, mu, ofu, false, lane) : few_fwd(rows, out, cf, tile, mu, ofu, false, lane);
       if (kCountDag) dag += __popcll(tile.mask & mu);
-      // nodes with more than eight in-links: add the rest to the stored entries
+      // nodes with more than eight in-links: add the rest to the staged entries
       const int p0 = __shfl(lr.p0, node, kWave), p1 = __shfl(lr.p1, node, kWave);
       for (int base = 8; __ballot(p0 + base < p1) != 0; base += 8) {
         const Tile extra = tile_request_idx(prev, tile_request_col(in_col, lr, c, base, lane, q));
@@ -1157,18 +1185,27 @@ fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_co
         if (kCountDag) dag += __popcll(extra.mask & mu);
       }
       __builtin_amdgcn_wave_barrier();
+      // lane = source: the nodes' sums are put together in LDS, in place of the accumulators (once every
+      // lane holds its values), as the tile's piece of the sigma array, and stored as whole lines
+      double val[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {  // lane = source: the node's sums go to its row
+      for (int i = 0; i < 8; ++i) val[i] = acc[i][lane];
+      __builtin_amdgcn_wave_barrier();
+      const TileSpan span = tile_span(me, nodes_active, c);
+      TOut* __restrict__ flat = reinterpret_cast<TOut*>(&acc[0][0]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
         const uint64_t newv = readlane64(me.mask, 8 * c + i);
         const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
         if (lane_in(newv)) {
-          const double a = acc[i][lane];
           const uint32_t e = of + rank_in(newv);
-          entry(out, e) = (TOut)a;
-          if (cf != nullptr) entry(cf, e) = recip(a);
-          inexact |= a >= kTwo53;
+          flat[e - span.of0] = (TOut)val[i];
+          if (cf != nullptr) entry(cf, e) = recip(val[i]);
+          inexact |= val[i] >= kTwo53;
         }
       }
+      __builtin_amdgcn_wave_barrier();
+      store_staged(out, flat, span, lane);
       __builtin_amdgcn_wave_barrier();
     }
     tile = tile_next;
@@ -1346,15 +1383,25 @@ bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_
         if (qe >= 0 && (extra.mask & mu) != 0) unsafeAtomicAdd(&pt[qe], te);
       }
       __builtin_amdgcn_wave_barrier();
+      // The coef rows of the tile's nodes are adjacent in memory: they are put together in LDS (in
+      // place of the accumulators, once every lane holds its values) and stored as whole lines.
+      double val[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {  // lane = source: the node's coef row
+      for (int i = 0; i < 8; ++i) {  // lane = source
+        val[i] = dm[i] * recip(sg[i]) + acc[i][lane];
+        if (kDemand && lane_in(readlane64(me.mask, 8 * c + i))) wd += dm[i];
+      }
+      __builtin_amdgcn_wave_barrier();
+      const TileSpan span = tile_span(me, nodes_active, c);
+      double* __restrict__ flat = &acc[0][0];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
         const uint64_t mu_i = readlane64(me.mask, 8 * c + i);
         const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, 8 * c + i);
-        if (lane_in(mu_i)) {
-          entry(cf, of + rank_in(mu_i)) = dm[i] * recip(sg[i]) + acc[i][lane];
-          if (kDemand) wd += dm[i];
-        }
+        if (lane_in(mu_i)) flat[of - span.of0 + rank_in(mu_i)] = val[i];
       }
+      __builtin_amdgcn_wave_barrier();
+      store_staged(cf, flat, span, lane);
       __builtin_amdgcn_wave_barrier();
     }
     tile = tile_next;
@@ -1468,11 +1515,13 @@ k_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, Gr
   if (f.here == 0) return;
   const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
   if (v0 >= gv.N) return;
-  __shared__ double s_acc[kWavesPerBlock][8][kWave];  // spread: [node of the tile][source]
+  // spread: accumulators, [node of the tile][source]; rows: the tile's piece of the sigma array
+  __shared__ double s_acc[kWavesPerBlock][8][kWave];
   const bool init_coef = gv.coef != nullptr && gv.dem == nullptr && f.after == 0;
   switch (pick_flavour(f.here, f.before, gv.N)) {
     case kFlavRows:
-      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0);
+      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0,
+                                     reinterpret_cast<TOut*>(&s_acc[threadIdx.x / kWave][0][0]));
       break;
     case kFlavSpread:
       fwd_spread<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, s_acc[threadIdx.x / kWave]);
