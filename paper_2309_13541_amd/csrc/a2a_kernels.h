@@ -155,27 +155,44 @@ __device__ __forceinline__ double xor_lanes(double x) {
   return b.d;
 }
 
+// The same for a 32-bit value (masks below 8 only).
+template <int kMask>
+__device__ __forceinline__ float xor_lanes(float x) {
+  static_assert(kMask == 1 || kMask == 2 || kMask == 4, "exchange inside a group of eight lanes");
+  const int a = __float_as_int(x);
+  int b;
+  if constexpr (kMask == 1) {
+    b = __builtin_amdgcn_mov_dpp(a, 0xB1, 0xF, 0xF, true);
+  } else if constexpr (kMask == 2) {
+    b = __builtin_amdgcn_mov_dpp(a, 0x4E, 0xF, 0xF, true);
+  } else {
+    b = __builtin_amdgcn_ds_swizzle(a, 0x1F | (kMask << 10));
+  }
+  return __int_as_float(b);
+}
+
 // Eight sums over groups of eight lanes at once.  x[i] is lane-local; on return lane l holds the
 // sum of x[l & 7] over the eight lanes 8*(l>>3) .. 8*(l>>3)+7.  Halving the value set at each
 // exchange step costs 4+2+1 exchanges instead of 8*3, in a fixed order (so results are
 // reproducible).
-__device__ __forceinline__ double group_sum8(const double (&x)[8], int lane) {
+template <typename T>
+__device__ __forceinline__ T group_sum8(const T (&x)[8], int lane) {
   const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
-  double y[4], z[2];
+  T y[4], z[2];
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    const double keep = b0 ? x[2 * k + 1] : x[2 * k];
-    const double send = b0 ? x[2 * k] : x[2 * k + 1];
+    const T keep = b0 ? x[2 * k + 1] : x[2 * k];
+    const T send = b0 ? x[2 * k] : x[2 * k + 1];
     y[k] = keep + xor_lanes<1>(send);
   }
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
-    const double keep = b1 ? y[2 * k + 1] : y[2 * k];
-    const double send = b1 ? y[2 * k] : y[2 * k + 1];
+    const T keep = b1 ? y[2 * k + 1] : y[2 * k];
+    const T send = b1 ? y[2 * k] : y[2 * k + 1];
     z[k] = keep + xor_lanes<2>(send);
   }
-  const double keep = b2 ? z[1] : z[0];
-  const double send = b2 ? z[0] : z[1];
+  const T keep = b2 ? z[1] : z[0];
+  const T send = b2 ? z[0] : z[1];
   return keep + xor_lanes<4>(send);  // lane l: sum of x[l & 7] over the eight lanes of its group
 }
 
@@ -568,17 +585,19 @@ __device__ __forceinline__ void store_staged(T* __restrict__ arr, const T* __res
 template <typename TIn, typename TOut>
 __device__ __forceinline__ bool fwd_finish(TOut* __restrict__ stage, uint32_t of0, double* __restrict__ cf,
                                            const NodeIdx& me, int node, const TIn (&x)[8]) {
-  double a = 0.0;
+  // A level kept in single precision has all its path counts below 2^24 (the host's bound), so every
+  // partial sum of these whole numbers is below 2^24 too: adding them as floats is exact.
+  TOut a = (TOut)0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) a += (double)hold(x[j]);
+  for (int j = 0; j < 8; ++j) a += (TOut)hold(x[j]);
   const uint64_t newv = readlane64(me.mask, node);
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
   bool big = false;
   if (lane_in(newv)) {
     const uint32_t e = of + rank_in(newv);
-    stage[e - of0] = (TOut)a;
-    if (cf != nullptr) entry(cf, e) = recip(a);
-    big = a >= kTwo53;
+    stage[e - of0] = a;
+    if (cf != nullptr) entry(cf, e) = recip((double)a);
+    if constexpr (sizeof(TOut) == 8) big = a >= kTwo53;
   }
   return big;
 }
@@ -874,15 +893,15 @@ __device__ __forceinline__ bool few_fwd(const TIn* __restrict__ rows, TOut* __re
     TIn xr[8];
     int mine;
     few_fetch8(rows, tl.mask, tl.off, rest, xr, lane & 7, mine);
-    double x[8];
+    TOut x[8];  // a level kept in single precision is summed in it: whole numbers below 2^24, exact
 #pragma unroll
-    for (int k = 0; k < 8; ++k) x[k] = (double)hold(xr[k]);
-    double a = group_sum8(x, lane);
-    if (left > 0 && !(add && a == 0.0)) {
-      if (add) a += (double)entry(out, e);
-      entry(out, e) = (TOut)a;
-      if (cf != nullptr) entry(cf, e) = recip(a);
-      big |= a >= kTwo53;
+    for (int k = 0; k < 8; ++k) x[k] = (TOut)hold(xr[k]);
+    TOut a = group_sum8(x, lane);
+    if (left > 0 && !(add && a == (TOut)0)) {
+      if (add) a += entry(out, e);
+      entry(out, e) = a;
+      if (cf != nullptr) entry(cf, e) = recip((double)a);
+      if constexpr (sizeof(TOut) == 8) big |= a >= kTwo53;
     }
     e += 8;
     left -= 8;
@@ -993,14 +1012,14 @@ __device__ __forceinline__ bool slot_fwd(const TIn* __restrict__ rows, TOut* __r
     const int s = slot_take8(rest, lane & 7);
     TIn x[8];
     slot_fetch8(rows, tl, s, x);
-    double a = 0.0;
+    TOut a = (TOut)0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a += (double)hold(x[j]);
-    if (s >= 0 && !(add && a == 0.0)) {
-      if (add) a += (double)entry(out, e);
-      entry(out, e) = (TOut)a;
-      if (cf != nullptr) entry(cf, e) = recip(a);
-      big |= a >= kTwo53;
+    for (int j = 0; j < 8; ++j) a += (TOut)hold(x[j]);
+    if (s >= 0 && !(add && a == (TOut)0)) {
+      if (add) a += entry(out, e);
+      entry(out, e) = a;
+      if (cf != nullptr) entry(cf, e) = recip((double)a);
+      if constexpr (sizeof(TOut) == 8) big |= a >= kTwo53;
     }
     e += 8;
   }
