@@ -286,6 +286,8 @@ struct GroupView {
   double* part;       // [G][Epad]      per-batch link loads
   size_t Epad;
   int N, Npad, Lcap, G, SB, bpb, nb64, inflight;
+  int split;          // waves that share a block of 64 nodes in k_fwd / k_bwd (1, 2, 4 or 8; above 1 the
+                      // kShared kernels are launched; 1 with demands and while shortest-path links are counted)
   int src_begin, src_count, batch0;
   int f32_levels;     // >= 1
   // Commodities of unequal demand (nullptr: every pair has demand 1): demand of source
@@ -489,6 +491,14 @@ struct Tile {
   uint32_t off;   // its row offset
 };
 
+// Which of the (up to) eight tiles of its 64 nodes a wave works on: first, first + step, ...  {0, 1}: all
+// of them, the normal case.  Where a topology is too small to fill the chip, `step` waves share a block of
+// 64 nodes (tile c of the block belongs to the wave with first = c mod step): the chain of dependent
+// memory requests that a wave goes through gets shorter by that factor.
+struct TileShare {
+  int first, step;
+};
+
 // In- or out-link range of the 64 nodes, one node per lane; nothing for nodes not on this level.
 struct LinkRange {
   int p0, p1;
@@ -606,7 +616,8 @@ __device__ __forceinline__ bool fwd_finish(TOut* __restrict__ stage, uint32_t of
 template <bool kCountDag, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv,
-         int level, bool init_coef, long long* __restrict__ misc, int g, int v0, TOut* __restrict__ stage) {
+         int level, bool init_coef, long long* __restrict__ misc, int g, int v0, TOut* __restrict__ stage,
+         const TileShare& ts) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
@@ -625,12 +636,12 @@ fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col,
   bool inexact = false;
   long long dag = 0;
   int q;
-  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
-  int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, ts.first, 0, lane, q));
+  int nb_next = ts.first + ts.step < 8 ? tile_request_col(in_col, lr, ts.first + ts.step, 0, lane, q) : -1;
 #pragma unroll 1
-  for (int c = 0; c < 8; ++c) {
-    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
-    nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+  for (int c = ts.first; c < 8; c += ts.step) {
+    const Tile tile_next = tile_request_idx(prev, c + ts.step < 8 ? nb_next : -1);
+    nb_next = c + 2 * ts.step < 8 ? tile_request_col(in_col, lr, c + 2 * ts.step, 0, lane, q) : -1;
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       TIn xa[8], xb[8];
       uint64_t m[8];
@@ -759,7 +770,7 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
 template <typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv,
-         int level, int g, int u0, double* __restrict__ sum8_buf) {
+         int level, int g, int u0, double* __restrict__ sum8_buf, const TileShare& ts) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -778,14 +789,15 @@ bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_co
     lr.p1 = out_ptr[u0 + lane + 1];
   }
   int q, q_next, q_nn;
-  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
-  int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, ts.first, 0, lane, q));
+  q_next = -1;
+  int nb_next = ts.first + ts.step < 8 ? tile_request_col(out_col, lr, ts.first + ts.step, 0, lane, q_next) : -1;
 #pragma unroll 1
-  for (int c = 0; c < 8; ++c) {
-    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+  for (int c = ts.first; c < 8; c += ts.step) {
+    const Tile tile_next = tile_request_idx(next, c + ts.step < 8 ? nb_next : -1);
     nb_next = -1;
     q_nn = -1;
-    if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    if (c + 2 * ts.step < 8) nb_next = tile_request_col(out_col, lr, c + 2 * ts.step, 0, lane, q_nn);
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       double xa[8], xb[8];
       uint64_t ma[8], mb[8];
@@ -1066,7 +1078,7 @@ __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* _
 template <bool kCountDag, bool kSlots, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
-        bool init_coef, long long* __restrict__ misc, int g, int v0) {
+        bool init_coef, long long* __restrict__ misc, int g, int v0, const TileShare& ts) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
@@ -1087,12 +1099,12 @@ fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, 
   bool inexact = false;
   int dag = 0;
   int q;
-  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
-  int nb_next = tiles > 1 ? tile_request_col(in_col, lr, 1, 0, lane, q) : -1;
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, ts.first, 0, lane, q));
+  int nb_next = ts.first + ts.step < tiles ? tile_request_col(in_col, lr, ts.first + ts.step, 0, lane, q) : -1;
 #pragma unroll 1
-  for (int c = 0; c < tiles; ++c) {
-    const Tile tile_next = tile_request_idx(prev, c + 1 < tiles ? nb_next : -1);
-    nb_next = c + 2 < tiles ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+  for (int c = ts.first; c < tiles; c += ts.step) {
+    const Tile tile_next = tile_request_idx(prev, c + ts.step < tiles ? nb_next : -1);
+    nb_next = c + 2 * ts.step < tiles ? tile_request_col(in_col, lr, c + 2 * ts.step, 0, lane, q) : -1;
     {
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
@@ -1163,7 +1175,8 @@ __device__ __forceinline__ void spread_link(const T* __restrict__ rows, const Ti
 template <bool kCountDag, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
-           bool init_coef, long long* __restrict__ misc, int g, int v0, double (*__restrict__ acc)[kWave]) {
+           bool init_coef, long long* __restrict__ misc, int g, int v0, double (*__restrict__ acc)[kWave],
+           const TileShare& ts) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
@@ -1182,12 +1195,12 @@ fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_co
   bool inexact = false;
   int dag = 0;
   int q;
-  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, 0, 0, lane, q));
-  int nb_next = tile_request_col(in_col, lr, 1, 0, lane, q);
+  Tile tile = tile_request_idx(prev, tile_request_col(in_col, lr, ts.first, 0, lane, q));
+  int nb_next = ts.first + ts.step < 8 ? tile_request_col(in_col, lr, ts.first + ts.step, 0, lane, q) : -1;
 #pragma unroll 1
-  for (int c = 0; c < 8; ++c) {
-    const Tile tile_next = tile_request_idx(prev, c + 1 < 8 ? nb_next : -1);
-    nb_next = c + 2 < 8 ? tile_request_col(in_col, lr, c + 2, 0, lane, q) : -1;
+  for (int c = ts.first; c < 8; c += ts.step) {
+    const Tile tile_next = tile_request_idx(prev, c + ts.step < 8 ? nb_next : -1);
+    nb_next = c + 2 * ts.step < 8 ? tile_request_col(in_col, lr, c + 2 * ts.step, 0, lane, q) : -1;
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i][lane] = 0.0;
@@ -1340,7 +1353,7 @@ __device__ __forceinline__ double spread_ordered_bwd(const double* __restrict__ 
 template <typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
-           int g, int u0, double (*__restrict__ acc)[kWave], TS (*__restrict__ sig)[kWave]) {
+           int g, int u0, double (*__restrict__ acc)[kWave], TS (*__restrict__ sig)[kWave], const TileShare& ts) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -1359,14 +1372,15 @@ bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_
     lr.p1 = out_ptr[u0 + lane + 1];
   }
   int q, q_next, q_nn;
-  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
-  int nb_next = tile_request_col(out_col, lr, 1, 0, lane, q_next);
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, ts.first, 0, lane, q));
+  q_next = -1;
+  int nb_next = ts.first + ts.step < 8 ? tile_request_col(out_col, lr, ts.first + ts.step, 0, lane, q_next) : -1;
 #pragma unroll 1
-  for (int c = 0; c < 8; ++c) {
-    const Tile tile_next = tile_request_idx(next, c + 1 < 8 ? nb_next : -1);
+  for (int c = ts.first; c < 8; c += ts.step) {
+    const Tile tile_next = tile_request_idx(next, c + ts.step < 8 ? nb_next : -1);
     nb_next = -1;
     q_nn = -1;
-    if (c + 2 < 8) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    if (c + 2 * ts.step < 8) nb_next = tile_request_col(out_col, lr, c + 2 * ts.step, 0, lane, q_nn);
     if (((nodes_active >> (8 * c)) & 0xffull) != 0) {
       TS sg_own[8];  // lane = source: sigma of the nodes' sources, all rows requested first
       double dm[8];  // and their demands
@@ -1433,7 +1447,7 @@ bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_
 template <bool kSlots, typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
-        int g, int u0) {
+        int g, int u0, const TileShare& ts) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -1454,14 +1468,14 @@ bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col
   int nid = u0 + lane;
   const int tiles = (compact_nodes(nodes_active, lane, me, lr, nid) + 7) >> 3;
   int q, q_next = -1, q_nn;
-  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, 0, 0, lane, q));
-  int nb_next = tiles > 1 ? tile_request_col(out_col, lr, 1, 0, lane, q_next) : -1;
+  Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, ts.first, 0, lane, q));
+  int nb_next = ts.first + ts.step < tiles ? tile_request_col(out_col, lr, ts.first + ts.step, 0, lane, q_next) : -1;
 #pragma unroll 1
-  for (int c = 0; c < tiles; ++c) {
-    const Tile tile_next = tile_request_idx(next, c + 1 < tiles ? nb_next : -1);
+  for (int c = ts.first; c < tiles; c += ts.step) {
+    const Tile tile_next = tile_request_idx(next, c + ts.step < tiles ? nb_next : -1);
     nb_next = -1;
     q_nn = -1;
-    if (c + 2 < tiles) nb_next = tile_request_col(out_col, lr, c + 2, 0, lane, q_nn);
+    if (c + 2 * ts.step < tiles) nb_next = tile_request_col(out_col, lr, c + 2 * ts.step, 0, lane, q_nn);
     {
       const int node = 8 * c + (lane >> 3);
       const uint64_t mu = shfl64(me.mask, node);
@@ -1522,69 +1536,99 @@ __host__ __device__ __forceinline__ int pick_flavour(long long here, long long o
   return here >= kSlotLanes * N ? kFlavSlots : kFlavFew;
 }
 
-// sigma of one level (1 .. deepest) for every batch of the group.  The batch's deepest level also
-// gets coef = 1 / sigma (unit demands: there is nothing to add to it).
+// One wave's share of a forward level: sigma of the 64 nodes v0 .. v0+63 (v0 < N) of batch g.  The
+// batch's deepest level also gets coef = 1 / sigma (unit demands: there is nothing to add to it).
+// acc: kFwdWaveDoubles doubles of LDS of this wave's own (spread: accumulators, [node of the tile]
+// [source]; rows: the tile's piece of the sigma array).  f: the batch's pair counts around the level.
+constexpr int kFwdWaveDoubles = 8 * kWave;
 template <bool kCountDag, typename TIn, typename TOut>
-__global__ void __launch_bounds__(kBlock)
-k_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
-      long long* __restrict__ misc) {
-  int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
-  const LevelFill f = level_fill(gv, g, level);
+__device__ __forceinline__ void
+fwd_wave(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
+         const LevelFill& f, long long* __restrict__ misc, int g, int v0, double* __restrict__ acc,
+         const TileShare& ts) {
   if (f.here == 0) return;
-  const int v0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (v0 >= gv.N) return;
-  // spread: accumulators, [node of the tile][source]; rows: the tile's piece of the sigma array
-  __shared__ double s_acc[kWavesPerBlock][8][kWave];
   const bool init_coef = gv.coef != nullptr && gv.dem == nullptr && f.after == 0;
   switch (pick_flavour(f.here, f.before, gv.N)) {
     case kFlavRows:
-      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0,
-                                     reinterpret_cast<TOut*>(&s_acc[threadIdx.x / kWave][0][0]));
+      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, reinterpret_cast<TOut*>(acc), ts);
       break;
     case kFlavSpread:
-      fwd_spread<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, s_acc[threadIdx.x / kWave]);
+      fwd_spread<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0,
+                                       reinterpret_cast<double(*)[kWave]>(acc), ts);
       break;
     case kFlavSlots:
-      fwd_few<kCountDag, true, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0);
+      fwd_few<kCountDag, true, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, ts);
       break;
     default:
-      fwd_few<kCountDag, false, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0);
+      fwd_few<kCountDag, false, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, ts);
       break;
   }
 }
 
-// coef and link loads of one level for every batch of the group.  With unit demands a batch's
-// deepest level is skipped: the forward pass left its coef.
-template <typename TS, bool kDemand>
+// sigma of one level (1 .. deepest) for every batch of the group.  kShared: gv.split waves share a
+// block of 64 nodes (a kernel of its own, so that the usual one keeps its constant loop bounds).
+template <bool kCountDag, typename TIn, typename TOut, bool kShared = false>
 __global__ void __launch_bounds__(kBlock)
-k_bwd(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
+k_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, GroupView gv, int level,
+      long long* __restrict__ misc) {
+  const int split = kShared ? gv.split : 1;
   int g, nblk;
-  if (!map_block(gv.G, gv.bpb, gv.inflight, g, nblk)) return;
-  const LevelFill f = level_fill(gv, g, level);
-  if (f.here == 0 || (!kDemand && f.after == 0)) return;
-  const int u0 = __builtin_amdgcn_readfirstlane((nblk * kWavesPerBlock + (int)(threadIdx.x / kWave)) * kWave);
-  if (u0 >= gv.N) return;
-  // rows: the eight 64-lane sums of a node; spread: accumulators and sigma, [node of the tile][source]
+  if (!map_block(gv.G, gv.bpb * split, gv.inflight, g, nblk)) return;
+  const int w = __builtin_amdgcn_readfirstlane(nblk * kWavesPerBlock + (int)(threadIdx.x / kWave));
+  const int v0 = w / split * kWave;
+  if (v0 >= gv.N) return;
+  const TileShare ts = {w % split, split};
+  __shared__ double s_acc[kWavesPerBlock][kFwdWaveDoubles];
+  fwd_wave<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, level_fill(gv, g, level), misc, g, v0,
+                                 s_acc[threadIdx.x / kWave], ts);
+}
+
+// One wave's share of a backward level: coef of the 64 nodes u0 .. u0+63 (u0 < N) of batch g and the
+// loads of their out-links.  With unit demands a batch's deepest level is skipped: the forward pass
+// left its coef.  buf: bwd_wave_doubles<TS>() doubles of LDS of this wave's own (rows: the eight
+// 64-lane sums of a node; spread: accumulators and sigma, [node of the tile][source]).  f: the batch's
+// pair counts around the level.
+template <typename TS>
+__host__ __device__ constexpr int bwd_wave_doubles() {
   constexpr int kSpreadDoubles = 8 * kWave + 8 * kWave * (int)sizeof(TS) / 8;
-  constexpr int kBufDoubles = kSpreadDoubles > kSum8Doubles ? kSpreadDoubles : kSum8Doubles;
-  __shared__ double s_buf[kWavesPerBlock][kBufDoubles];
-  double* buf = s_buf[threadIdx.x / kWave];
+  return kSpreadDoubles > kSum8Doubles ? kSpreadDoubles : kSum8Doubles;
+}
+template <typename TS, bool kDemand>
+__device__ __forceinline__ void
+bwd_wave(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
+         const LevelFill& f, int g, int u0, double* __restrict__ buf, const TileShare& ts) {
+  if (f.here == 0 || (!kDemand && f.after == 0)) return;
   switch (pick_flavour(f.here, f.after, gv.N)) {
     case kFlavRows:
-      bwd_rows<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, buf);
+      bwd_rows<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, buf, ts);
       break;
     case kFlavSpread:
       bwd_spread<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, reinterpret_cast<double(*)[kWave]>(buf),
-                              reinterpret_cast<TS(*)[kWave]>(buf + 8 * kWave));
+                              reinterpret_cast<TS(*)[kWave]>(buf + 8 * kWave), ts);
       break;
     case kFlavSlots:
-      bwd_few<true, TS, kDemand>(out_ptr, out_col, gv, level, g, u0);
+      bwd_few<true, TS, kDemand>(out_ptr, out_col, gv, level, g, u0, ts);
       break;
     default:
-      bwd_few<false, TS, kDemand>(out_ptr, out_col, gv, level, g, u0);
+      bwd_few<false, TS, kDemand>(out_ptr, out_col, gv, level, g, u0, ts);
       break;
   }
+}
+
+// coef and link loads of one level for every batch of the group.  kShared: as in k_fwd.
+template <typename TS, bool kDemand, bool kShared = false>
+__global__ void __launch_bounds__(kBlock)
+k_bwd(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, GroupView gv, int level) {
+  static_assert(!(kDemand && kShared), "a block's demand x distance slot belongs to one wave");
+  const int split = kShared ? gv.split : 1;
+  int g, nblk;
+  if (!map_block(gv.G, gv.bpb * split, gv.inflight, g, nblk)) return;
+  const int w = __builtin_amdgcn_readfirstlane(nblk * kWavesPerBlock + (int)(threadIdx.x / kWave));
+  const int u0 = w / split * kWave;
+  if (u0 >= gv.N) return;
+  const TileShare ts = {w % split, split};
+  __shared__ double s_buf[kWavesPerBlock][bwd_wave_doubles<TS>()];
+  bwd_wave<TS, kDemand>(out_ptr, out_col, gv, level, level_fill(gv, g, level), g, u0, s_buf[threadIdx.x / kWave], ts);
 }
 
 // load[a] = (first group ? 0 : load[a]) + part[0][a] + part[1][a] + ... in that order.

@@ -250,6 +250,7 @@ struct Run {
   int src_begin, src_count;
   const double* demand = nullptr;  // [N][src_count] by target, or nullptr: every pair has demand 1
   int inflight = kXcd;  // batches in flight = XCDs: one batch's node blocks per XCD at a time
+  int split = 1;        // waves per block of 64 nodes in the forward / backward kernels (pick_split)
   mutable std::vector<double> lanes_per_node;  // profiling only: per level of the current group, pairs / (G*N)
   bool few(int level) const {
     return level >= 0 && level < (int)lanes_per_node.size() && lanes_per_node[level] > 0.0 &&
@@ -287,6 +288,7 @@ struct Run {
     gv.bpb = L.bpb;
     gv.nb64 = L.nb64;
     gv.inflight = inflight;
+    gv.split = split;
     gv.src_begin = src_begin;
     gv.src_count = src_count;
     gv.batch0 = batch0;
@@ -297,6 +299,18 @@ struct Run {
     return gv;
   }
 };
+
+// A group that cannot fill the chip with one wave per 64 nodes lets 2, 4 or 8 waves share each block of
+// 64 nodes (a tile of eight nodes is the unit): a wave's chain of dependent memory requests, which
+// is what a launch of a small group costs, gets that much shorter.  Not with demands, not while
+// shortest-path links are counted (see GroupView).
+constexpr int kSplitWaves = 8192;
+int pick_split(const a2a_topo* t, int G, int nb64, bool demand) {
+  if (demand || t->prof_mode == 2) return 1;
+  int split = 1;
+  while (split < 8 && (long long)G * nb64 * split * 2 <= kSplitWaves) split *= 2;
+  return split;
+}
 
 // BFS of one group: levels 1 .. top (the handle's deepest level, one more when the backward pass
 // will look at the empty level after a batch's last one).
@@ -362,7 +376,7 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     if (idx_depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * idx_depth), kWave, 0, r.st>>>(gv, idx_depth);
     k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, idx_depth);
   }
-  const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
+  const unsigned grid = grid_for(gv.G, L.bpb * gv.split, r.inflight);
   for (int l = 1; l <= depth; ++l) {
     const int cls = r.few(l) ? PROF_FWD_FEW : (r.few(l - 1) ? PROF_FWD_SPREAD : PROF_FWD);
     ProfScope ps(t, cls, r.st, l);
@@ -370,13 +384,20 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     auto launch = [&](auto kernel) {
       kernel<<<grid, kBlock, 0, r.st>>>(t->d_in_ptr, t->d_in_col, gv, l, r.misc());
     };
-    // precision of the level gathered from and of the one written
+    // precision of the level gathered from and of the one written; waves sharing blocks of nodes or not
+    const bool shared = gv.split > 1;  // never while counting
     if (r.narrow(l))
-      count ? launch(k_fwd<true, float, float>) : launch(k_fwd<false, float, float>);
+      count    ? launch(k_fwd<true, float, float>)
+      : shared ? launch(k_fwd<false, float, float, true>)
+               : launch(k_fwd<false, float, float>);
     else if (r.narrow(l - 1))
-      count ? launch(k_fwd<true, float, double>) : launch(k_fwd<false, float, double>);
+      count    ? launch(k_fwd<true, float, double>)
+      : shared ? launch(k_fwd<false, float, double, true>)
+               : launch(k_fwd<false, float, double>);
     else
-      count ? launch(k_fwd<true, double, double>) : launch(k_fwd<false, double, double>);
+      count    ? launch(k_fwd<true, double, double>)
+      : shared ? launch(k_fwd<false, double, double, true>)
+               : launch(k_fwd<false, double, double>);
     if (t->prof_mode != 0 && l < 64 && r.narrow(l - 1)) t->prof_narrow |= 1ull << l;
   }
   HIP_TRY(hipGetLastError());
@@ -606,6 +627,7 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
   const int nb = (src_count + 63) / 64;
   const int tiles = L.Npad / kWave;
   for (int b0 = 0; b0 < nb; b0 += L.G) {
+    r.split = pick_split(t, nb - b0 < L.G ? nb - b0 : L.G, L.nb64, false);
     const GroupView gv = r.view(b0, nb - b0 < L.G ? nb - b0 : L.G);
     const int depth = t->level_bound;
     rc = run_bfs(r, gv, depth);
@@ -667,6 +689,7 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
   HIP_TRY(zero_async(r.misc(), 64, st));
   const int nb = (src_count + 63) / 64;
   for (int b0 = 0; b0 < nb; b0 += L.G) {
+    r.split = pick_split(t, nb - b0 < L.G ? nb - b0 : L.G, L.nb64, demand != nullptr);
     const GroupView gv = r.view(b0, nb - b0 < L.G ? nb - b0 : L.G);
     const int depth = t->level_bound;
     rc = run_bfs(r, gv, demand ? depth + 1 : depth);
@@ -676,7 +699,7 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
     if (t->E > 0) {
       HIP_TRY(zero_async(gv.part, (size_t)gv.G * L.Epad * 8, st));
       if (demand) HIP_TRY(zero_async(gv.wpart, (size_t)gv.G * L.nb64 * 8, st));
-      const unsigned grid = grid_for(gv.G, L.bpb, r.inflight);
+      const unsigned grid = grid_for(gv.G, L.bpb * gv.split, r.inflight);
       // Unit demands: a batch's deepest level has no successors and its coef = 1/sigma was left by
       // the forward pass, nothing to add (the kernel skips it).  With demands it is visited like the others.
       for (int l = demand ? depth : depth - 1; l >= 0; --l) {
@@ -685,6 +708,8 @@ int link_loads(const a2a_topo* t, int32_t src_begin, int32_t src_count, const do
         auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(t->d_out_ptr, t->d_out_col, gv, l); };
         if (demand)  // precision of this level's sigma
           r.narrow(l) ? launch(k_bwd<float, true>) : launch(k_bwd<double, true>);
+        else if (gv.split > 1)
+          r.narrow(l) ? launch(k_bwd<float, false, true>) : launch(k_bwd<double, false, true>);
         else
           r.narrow(l) ? launch(k_bwd<float, false>) : launch(k_bwd<double, false>);
       }
