@@ -617,22 +617,15 @@ template <bool kCountDag, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_rows(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv,
          int level, bool init_coef, long long* __restrict__ misc, int g, int v0, TOut* __restrict__ stage,
-         const TileShare& ts) {
+         const TileShare& ts, const NodeIdx& me, const LinkRange& lr) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
   TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  LinkRange lr;
-  lr.p0 = lr.p1 = 0;
-  if (me.mask != 0) {
-    lr.p0 = in_ptr[v0 + lane];
-    lr.p1 = in_ptr[v0 + lane + 1];
-  }
   bool inexact = false;
   long long dag = 0;
   int q;
@@ -770,7 +763,8 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
 template <typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv,
-         int level, int g, int u0, double* __restrict__ sum8_buf, const TileShare& ts) {
+         int level, int g, int u0, double* __restrict__ sum8_buf, const TileShare& ts, const NodeIdx& me,
+         const LinkRange& lr) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -779,15 +773,8 @@ bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_co
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
   double wd = 0.0;  // this lane's source: demands met
-  const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  LinkRange lr;
-  lr.p0 = lr.p1 = 0;
-  if (me.mask != 0) {
-    lr.p0 = out_ptr[u0 + lane];
-    lr.p1 = out_ptr[u0 + lane + 1];
-  }
   int q, q_next, q_nn;
   Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, ts.first, 0, lane, q));
   q_next = -1;
@@ -1078,22 +1065,15 @@ __device__ __forceinline__ double slot_bwd(const TS* __restrict__ dat, double* _
 template <bool kCountDag, bool kSlots, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_few(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
-        bool init_coef, long long* __restrict__ misc, int g, int v0, const TileShare& ts) {
+        bool init_coef, long long* __restrict__ misc, int g, int v0, const TileShare& ts, NodeIdx me, LinkRange lr) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
   TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  LinkRange lr;
-  lr.p0 = lr.p1 = 0;
-  if (me.mask != 0) {
-    lr.p0 = in_ptr[v0 + lane];
-    lr.p1 = in_ptr[v0 + lane + 1];
-  }
   int nid = v0 + lane;
   const int tiles = (compact_nodes(nodes_active, lane, me, lr, nid) + 7) >> 3;
   bool inexact = false;
@@ -1176,22 +1156,15 @@ template <bool kCountDag, typename TIn, typename TOut>
 __device__ __forceinline__ void
 fwd_spread(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
            bool init_coef, long long* __restrict__ misc, int g, int v0, double (*__restrict__ acc)[kWave],
-           const TileShare& ts) {
+           const TileShare& ts, const NodeIdx& me, const LinkRange& lr) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ prev = cur - gv.Npad;
   const TIn* __restrict__ rows = sigma_rows<TIn>(gv, g);
   TOut* __restrict__ out = sigma_rows<TOut>(gv, g);
   double* __restrict__ cf = init_coef ? gv.coef + (size_t)g * gv.Npad * 64 : nullptr;
-  const NodeIdx me = load_idx(cur + v0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  LinkRange lr;
-  lr.p0 = lr.p1 = 0;
-  if (me.mask != 0) {
-    lr.p0 = in_ptr[v0 + lane];
-    lr.p1 = in_ptr[v0 + lane + 1];
-  }
   bool inexact = false;
   int dag = 0;
   int q;
@@ -1353,7 +1326,8 @@ __device__ __forceinline__ double spread_ordered_bwd(const double* __restrict__ 
 template <typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
-           int g, int u0, double (*__restrict__ acc)[kWave], TS (*__restrict__ sig)[kWave], const TileShare& ts) {
+           int g, int u0, double (*__restrict__ acc)[kWave], TS (*__restrict__ sig)[kWave], const TileShare& ts,
+           const NodeIdx& me, const LinkRange& lr) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -1362,15 +1336,8 @@ bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
   double wd = 0.0;
-  const NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  LinkRange lr;
-  lr.p0 = lr.p1 = 0;
-  if (me.mask != 0) {
-    lr.p0 = out_ptr[u0 + lane];
-    lr.p1 = out_ptr[u0 + lane + 1];
-  }
   int q, q_next, q_nn;
   Tile tile = tile_request_idx(next, tile_request_col(out_col, lr, ts.first, 0, lane, q));
   q_next = -1;
@@ -1447,7 +1414,7 @@ bwd_spread(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_
 template <bool kSlots, typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
-        int g, int u0, const TileShare& ts) {
+        int g, int u0, const TileShare& ts, NodeIdx me, LinkRange lr) {
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -1456,15 +1423,8 @@ bwd_few(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col
   double* __restrict__ pt = gv.part + (size_t)g * gv.Epad;
   const double* __restrict__ dem = kDemand ? demand_rows(gv, g) : nullptr;
   double wd = 0.0;
-  NodeIdx me = load_idx(cur + u0 + lane);
   const uint64_t nodes_active = __ballot(me.mask != 0);
   if (nodes_active == 0) return;
-  LinkRange lr;
-  lr.p0 = lr.p1 = 0;
-  if (me.mask != 0) {
-    lr.p0 = out_ptr[u0 + lane];
-    lr.p1 = out_ptr[u0 + lane + 1];
-  }
   int nid = u0 + lane;
   const int tiles = (compact_nodes(nodes_active, lane, me, lr, nid) + 7) >> 3;
   int q, q_next = -1, q_nn;
@@ -1546,21 +1506,33 @@ __device__ __forceinline__ void
 fwd_wave(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, const GroupView& gv, int level,
          const LevelFill& f, long long* __restrict__ misc, int g, int v0, double* __restrict__ acc,
          const TileShare& ts) {
+  // The wave's own index entries and in-link ranges are requested before the pair counts are looked at:
+  // one round trip to memory less on the critical path of a small launch (always in bounds; what they
+  // hold on a level the batch does not have is never used).
+  const int lane = lane_id();
+  const NodeIdx me = load_idx(gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad + v0 + lane);
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (v0 + lane < gv.N) {
+    lr.p0 = in_ptr[v0 + lane];
+    lr.p1 = in_ptr[v0 + lane + 1];
+  }
   if (f.here == 0) return;
+  if (me.mask == 0) lr.p0 = lr.p1 = 0;  // nothing for nodes not on this level
   const bool init_coef = gv.coef != nullptr && gv.dem == nullptr && f.after == 0;
   switch (pick_flavour(f.here, f.before, gv.N)) {
     case kFlavRows:
-      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, reinterpret_cast<TOut*>(acc), ts);
+      fwd_rows<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, reinterpret_cast<TOut*>(acc), ts, me, lr);
       break;
     case kFlavSpread:
       fwd_spread<kCountDag, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0,
-                                       reinterpret_cast<double(*)[kWave]>(acc), ts);
+                                       reinterpret_cast<double(*)[kWave]>(acc), ts, me, lr);
       break;
     case kFlavSlots:
-      fwd_few<kCountDag, true, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, ts);
+      fwd_few<kCountDag, true, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, ts, me, lr);
       break;
     default:
-      fwd_few<kCountDag, false, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, ts);
+      fwd_few<kCountDag, false, TIn, TOut>(in_ptr, in_col, gv, level, init_coef, misc, g, v0, ts, me, lr);
       break;
   }
 }
@@ -1597,20 +1569,29 @@ template <typename TS, bool kDemand>
 __device__ __forceinline__ void
 bwd_wave(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv, int level,
          const LevelFill& f, int g, int u0, double* __restrict__ buf, const TileShare& ts) {
+  const int lane = lane_id();  // as in fwd_wave: requested before the pair counts are looked at
+  const NodeIdx me = load_idx(gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad + u0 + lane);
+  LinkRange lr;
+  lr.p0 = lr.p1 = 0;
+  if (u0 + lane < gv.N) {
+    lr.p0 = out_ptr[u0 + lane];
+    lr.p1 = out_ptr[u0 + lane + 1];
+  }
   if (f.here == 0 || (!kDemand && f.after == 0)) return;
+  if (me.mask == 0) lr.p0 = lr.p1 = 0;
   switch (pick_flavour(f.here, f.after, gv.N)) {
     case kFlavRows:
-      bwd_rows<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, buf, ts);
+      bwd_rows<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, buf, ts, me, lr);
       break;
     case kFlavSpread:
       bwd_spread<TS, kDemand>(out_ptr, out_col, gv, level, g, u0, reinterpret_cast<double(*)[kWave]>(buf),
-                              reinterpret_cast<TS(*)[kWave]>(buf + 8 * kWave), ts);
+                              reinterpret_cast<TS(*)[kWave]>(buf + 8 * kWave), ts, me, lr);
       break;
     case kFlavSlots:
-      bwd_few<true, TS, kDemand>(out_ptr, out_col, gv, level, g, u0, ts);
+      bwd_few<true, TS, kDemand>(out_ptr, out_col, gv, level, g, u0, ts, me, lr);
       break;
     default:
-      bwd_few<false, TS, kDemand>(out_ptr, out_col, gv, level, g, u0, ts);
+      bwd_few<false, TS, kDemand>(out_ptr, out_col, gv, level, g, u0, ts, me, lr);
       break;
   }
 }
