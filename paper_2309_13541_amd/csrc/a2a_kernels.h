@@ -432,15 +432,20 @@ __global__ void __launch_bounds__(kWave) k_scan_blocks(GroupView gv, int depth) 
 // Index array from the BFS masks: idxb[g][l][v] = { L_l[v], first entry of the row }.
 // Thread (node, k) as in the BFS; the row offsets are an exclusive prefix over nodes for each
 // batch k (three shuffle steps across the 8 nodes of a wave, then across the 8 waves via LDS).
-__global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int depth) {
-  int sb, nblk;
-  if (!map_block(gv.SB, gv.nb64, kXcd, sb, nblk)) return;
+// A workgroup takes `levels` consecutive levels of its 64 nodes (all of them in a large group; one
+// each, in as many workgroups, where the group is too small to fill the chip otherwise).
+__global__ void __launch_bounds__(kBfsBlock) k_write_offsets(GroupView gv, int depth, int levels) {
+  const int chunks = (depth + levels) / levels;  // levels 0 .. depth
+  int sb, unit;
+  if (!map_block(gv.SB, gv.nb64 * chunks, kXcd, sb, unit)) return;
+  const int nblk = unit / chunks, l0 = unit % chunks * levels;
+  const int l1 = min(depth, l0 + levels - 1);
   __shared__ int s_w[kBfsWaves][kSub];
   __shared__ NodeIdx s_n[kSub][kBfsNodes + 1];
   const int t = (int)threadIdx.x, lane = lane_id(), wid = t / kWave;
   const int v = nblk * kBfsNodes + t / kSub, k = t % kSub;
   const int g = sb * kSub + k;
-  for (int l = 0; l <= depth; ++l) {
+  for (int l = l0; l <= l1; ++l) {
     const uint64_t m = gv.bm[bm_at(gv, sb, l, v, k)];
     NodeIdx n;
     n.mask = m;
@@ -1619,7 +1624,15 @@ k_reduce_part(const double* __restrict__ part, size_t Epad, int G, long long E, 
   const long long a = (long long)blockIdx.x * kBlock + threadIdx.x;
   if (a >= E) return;
   double s = first ? 0.0 : load[a];
-  for (int g = 0; g < G; ++g) s += part[(size_t)g * Epad + a];
+  int g = 0;
+  for (; g + 16 <= G; g += 16) {  // sixteen requests in flight, added in batch order
+    double x[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x[k] = part[(size_t)(g + k) * Epad + a];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) s += x[k];
+  }
+  for (; g < G; ++g) s += part[(size_t)g * Epad + a];
   load[a] = s;
 }
 

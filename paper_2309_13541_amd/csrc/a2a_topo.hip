@@ -374,7 +374,10 @@ int run_fwd(const Run& r, const GroupView& gv, int depth) {
     const int idx_depth = gv.dem != nullptr ? depth + 1 : depth;
     ProfScope ps(t, PROF_OFFSETS, r.st);
     if (idx_depth >= 1) k_scan_blocks<<<(unsigned)(gv.G * idx_depth), kWave, 0, r.st>>>(gv, idx_depth);
-    k_write_offsets<<<grid_for(gv.SB, L.nb64), kBfsBlock, 0, r.st>>>(gv, idx_depth);
+    // one workgroup per (super-batch, 64 nodes) works through all levels, unless that leaves most of the chip idle
+    const int levels = (long long)gv.SB * L.nb64 >= 2048 ? idx_depth + 1 : 1;
+    const int chunks = (idx_depth + levels) / levels;
+    k_write_offsets<<<grid_for(gv.SB, L.nb64 * chunks), kBfsBlock, 0, r.st>>>(gv, idx_depth, levels);
   }
   const unsigned grid = grid_for(gv.G, L.bpb * gv.split, r.inflight);
   for (int l = 1; l <= depth; ++l) {
