@@ -1728,6 +1728,84 @@ k_extract_dist_planes(GroupView gv, int depth, int planes, int32_t* __restrict__
     atomicAdd((unsigned long long*)&dist_sum[row0 + lane], (unsigned long long)mine);
 }
 
+// The same for depth < 128 with the loop over the sources taken eight at a time: the eight bits of a
+// plane that belong to sources j0 .. j0+7 are spread to eight bytes (one shift-or pair, two masks),
+// so that three or four instructions per plane build eight distances at once, packed in two words;
+// a source the node has not been reached from gets the byte 0xFF, which the sign-extending byte
+// extract turns into -1.  kPlanes (compile time: no branches in the loop) >= number of bits of the
+// depth; planes beyond it stay empty.  kSum: per-source distance sums as well.
+__device__ __forceinline__ uint32_t spread_bits4(uint32_t t, uint32_t pick) {
+  // t: a byte repeated four times; pick: 0x08040201 or 0x80402010.  Byte i of the result = bit (i or i+4).
+  return (((t & pick) + 0x7F7F7F7Fu) >> 7) & 0x01010101u;
+}
+template <int kPlanes, bool kSum>
+__global__ void __launch_bounds__(kBlock)
+k_extract_dist_packed(GroupView gv, int depth, int32_t* __restrict__ dist, long long* __restrict__ dist_sum) {
+  static_assert(kPlanes >= 1 && kPlanes <= 7, "a distance and the mark for unreachable share a signed byte");
+  const unsigned i = blockIdx.x / kXcd;  // workgroup order as in k_extract_dist_planes
+  const int k = (int)(i % kSub);
+  const int nblk = (int)((i / kSub) % (unsigned)gv.bpb);
+  const int sb = (int)(i / kSub / (unsigned)gv.bpb) * kXcd + (int)(blockIdx.x % kXcd);
+  const int g = sb * kSub + k;
+  if (g >= gv.G) return;
+  const int v = nblk * kBlock + (int)threadIdx.x;  // < Npad: the mask arrays are padded with zeros
+  const int lane = lane_id();
+  uint64_t B[kPlanes], R = 0;
+#pragma unroll
+  for (int p = 0; p < kPlanes; ++p) B[p] = 0;
+  for (int l = 0; l <= depth; ++l) {
+    const uint64_t m = gv.bm[bm_at(gv, sb, l, v, k)];
+    R |= m;
+#pragma unroll
+    for (int p = 0; p < kPlanes; ++p)
+      if ((l >> p) & 1) B[p] |= m;
+  }
+  const int row0 = (gv.batch0 + g) * 64;
+  const int cnt = min(64, gv.src_count - row0);
+  const bool live = v < gv.N;  // nodes past N: all masks 0, nothing stored, nothing added
+  int mine = 0;                // lane j: distance sum of source j over this wave's nodes
+#pragma unroll
+  for (int j0 = 0; j0 < 64; j0 += 8) {
+    if (j0 >= cnt) break;  // the same in all lanes
+    uint32_t lo = 0, hi = 0;  // byte i: distance of source j0+i / j0+4+i
+#pragma unroll
+    for (int p = 0; p < kPlanes; ++p) {
+      uint32_t t = (uint32_t)(B[p] >> j0) & 0xFFu;
+      t |= t << 8;
+      t |= t << 16;
+      lo |= spread_bits4(t, 0x08040201u) << p;
+      hi |= spread_bits4(t, 0x80402010u) << p;
+    }
+    if (dist != nullptr) {
+      uint32_t t = (uint32_t)(~R >> j0) & 0xFFu;  // not reached
+      t |= t << 8;
+      t |= t << 16;
+      const uint32_t nlo = spread_bits4(t, 0x08040201u), nhi = spread_bits4(t, 0x80402010u);
+      const uint32_t wlo = lo | ((nlo << 8) - nlo), whi = hi | ((nhi << 8) - nhi);  // 0x01 -> 0xFF
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (j0 + e < cnt) {  // the same in all lanes; false only in a call's last, ragged batch
+          int32_t* __restrict__ row = dist + (size_t)(row0 + j0 + e) * (size_t)gv.N;
+          const int d = __builtin_amdgcn_sbfe((int)(e < 4 ? wlo : whi), 8 * (e & 3), 8);
+          if (live) row[v] = d;
+        }
+      }
+    }
+    if (kSum) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int sum = 0;
+#pragma unroll
+        for (int p = 0; p < kPlanes; ++p)
+          sum += __popcll(__builtin_amdgcn_ballot_w64(((B[p] >> (j0 + e)) & 1ull) != 0)) << p;
+        if (lane == j0 + e) mine = sum;
+      }
+    }
+  }
+  if (kSum && lane < cnt && mine != 0)
+    atomicAdd((unsigned long long*)&dist_sum[row0 + lane], (unsigned long long)mine);
+}
+
 // sigma[s][v] from the level-compact rows, transposed through LDS.  One wave per tile.
 __global__ void __launch_bounds__(kWave)
 k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_out) {

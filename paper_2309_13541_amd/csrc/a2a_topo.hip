@@ -643,7 +643,16 @@ int a2a_distances(const a2a_topo* t, int32_t src_begin, int32_t src_count, int32
     }
     if (dist || dist_sum) {
       ProfScope ps(t, PROF_EXTRACT, st);
-      if (depth < 256) {
+      if (depth < 128) {  // eight sources at a time, the number of bit planes fixed at compile time
+        const unsigned grid = grid_for(gv.SB, L.bpb * kSub);
+        auto launch = [&](auto kernel) { kernel<<<grid, kBlock, 0, st>>>(gv, depth, dist, (long long*)dist_sum); };
+        if (depth < 8)
+          dist_sum ? launch(k_extract_dist_packed<3, true>) : launch(k_extract_dist_packed<3, false>);
+        else if (depth < 32)
+          dist_sum ? launch(k_extract_dist_packed<5, true>) : launch(k_extract_dist_packed<5, false>);
+        else
+          dist_sum ? launch(k_extract_dist_packed<7, true>) : launch(k_extract_dist_packed<7, false>);
+      } else if (depth < 256) {
         int planes = 0;
         while ((depth >> planes) != 0) ++planes;
         k_extract_dist_planes<<<grid_for(gv.SB, L.bpb * kSub), kBlock, 0, st>>>(gv, depth, planes, dist,
