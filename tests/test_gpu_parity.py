@@ -101,6 +101,14 @@ SMALL.update({
     "torus3x3x3": gen.torus([3, 3, 3]),
     "ring_odd_131": gen.ring(131),              # diameter 130, N not a multiple of 64
     "biring_200": gen.bidirectional_ring(200),  # diameter 100 = N/2
+    # the distance output builds 3, 5 or 7 bit planes (deepest level below 8, 32, 128), one source at a time up to
+    # 255, through an LDS tile beyond: both sides of every limit
+    "ring_8": gen.ring(8),
+    "ring_9": gen.ring(9),
+    "ring_32": gen.ring(32),
+    "ring_33": gen.ring(33),
+    "ring_128": gen.ring(128),
+    "ring_129": gen.ring(129),
     "ring_255": gen.ring(255),                  # diameter 254
     "ring_256": gen.ring(256),                  # diameter 255: deepest that the bit-plane distance output takes
     "ring_300": gen.ring(300),
