@@ -204,6 +204,9 @@ __device__ __forceinline__ T group_sum8(const T (&x)[8], int lane) {
 // go through the LDS pipeline.  `buf` is this wave's kSum8Doubles doubles of LDS.
 constexpr int kSum8Row = kWave + 1;
 constexpr int kSum8Doubles = 8 * kSum8Row;
+// LDS of a wave of the backward kernel: 8 KB.  Rows layout: the eight sums, then the staged coef rows of a tile.
+constexpr int kBwdDoubles = 16 * kWave;
+constexpr int kStageDoubles = kBwdDoubles - kSum8Doubles;
 __device__ __forceinline__ double wave_sum8_lds(const double (&x)[8], int lane, double* buf) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) buf[j * kSum8Row + lane] = x[j];
@@ -584,12 +587,14 @@ __device__ __forceinline__ TileSpan tile_span(const NodeIdx& me, uint64_t nodes_
 }
 
 // The span's entries from their copy in LDS (stage[0] = entry of0), 64 at a time; every store but the
-// first starts on a 128-byte boundary of the array, so whole lines go out.
+// first starts on a 128-byte boundary of the array, so whole lines go out.  The stores are marked
+// non-temporal: the rows are read again by a later launch only, and left in the L2 they push out the
+// index entries that this launch keeps coming back to.
 template <typename T>
 __device__ __forceinline__ void store_staged(T* __restrict__ arr, const T* __restrict__ stage, TileSpan t, int lane) {
   constexpr uint32_t kPerLine = 128 / sizeof(T);
   for (int k = lane - (int)(t.of0 & (kPerLine - 1)); (int)t.of0 + k < (int)t.end; k += kWave)
-    if (k >= 0) entry(arr, t.of0 + (uint32_t)k) = stage[k];
+    if (k >= 0) __builtin_nontemporal_store(stage[k], &entry(arr, t.of0 + (uint32_t)k));
 }
 
 // One level of sigma(s,v) = sum over in-links (u,v) with D(s,u) = D(s,v) - 1 of sigma(s,u).
@@ -742,11 +747,14 @@ __device__ __forceinline__ TS own_sigma(const TS* __restrict__ dat, const NodeId
 }
 
 // coef of a node from its sigma and the gathered coef rows (x, overwritten by the products that
-// the link loads are made of); `add`: further round of a node with more than eight links.
+// the link loads are made of); `add`: further round of a node with more than eight links.  The coef
+// goes to `stage` (unless null), the LDS copy of the coef rows of the tile's nodes (entry of0 of the
+// batch's array onwards), which the caller stores when the tile is done.
 template <typename TS>
 __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const NodeIdx& me, int node, int i, TS sigma,
                                              double dem, double (&x)[8], const uint64_t (&m)[8], int pairs, bool add,
-                                             int lane, double tot_l, double* sum8_buf) {
+                                             int lane, double tot_l, double* sum8_buf, double* __restrict__ stage,
+                                             uint32_t of0) {
   const double s = (double)hold(sigma);
   double a = 0.0;
 #pragma unroll
@@ -757,7 +765,7 @@ __device__ __forceinline__ double bwd_finish(double* __restrict__ cf, const Node
   const uint64_t mu = readlane64(me.mask, node);
   const uint32_t of = (uint32_t)__builtin_amdgcn_readlane((int)me.off, node);
   if (lane_in(mu)) {
-    double& e = entry(cf, of + rank_in(mu));
+    double& e = stage != nullptr ? stage[of - of0 + rank_in(mu)] : entry(cf, of + rank_in(mu));
     e = add ? e + a : dem * recip(s) + a;
   }
   if (pairs != 0) tot_l = link_sums(x, m, pairs, i, lane, tot_l, sum8_buf);
@@ -770,6 +778,7 @@ __device__ __forceinline__ void
 bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_col, const GroupView& gv,
          int level, int g, int u0, double* __restrict__ sum8_buf, const TileShare& ts, const NodeIdx& me,
          const LinkRange& lr) {
+  double* const stage_buf = sum8_buf + kSum8Doubles;  // kStageDoubles doubles
   const int lane = lane_id();
   const NodeIdx* __restrict__ cur = gv.idxb + ((size_t)g * gv.Lcap + level) * gv.Npad;
   const NodeIdx* __restrict__ next = cur + gv.Npad;
@@ -794,6 +803,10 @@ bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_co
       double xa[8], xb[8];
       uint64_t ma[8], mb[8];
       double tot_l = 0.0;  // lane 8i+j: load of out-link j of node i
+      // The coef rows of the tile's nodes are adjacent in memory: all but the very longest spans are put
+      // together in LDS and stored as whole lines (store_staged), the others entry by entry.
+      const TileSpan span = tile_span(me, nodes_active, c);
+      double* __restrict__ stage = span.end - span.of0 <= (uint32_t)kStageDoubles ? stage_buf : nullptr;
       TS sa = own_sigma(dat, me, 8 * c), sb;
       double da = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c, lane), db;
       int pa = gather8(cf, tile, 0, readlane64(me.mask, 8 * c), xa, ma), pb;
@@ -802,14 +815,14 @@ bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_co
         sb = own_sigma(dat, me, 8 * c + i + 1);
         db = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c + i + 1, lane);
         pb = gather8(cf, tile, i + 1, readlane64(me.mask, 8 * c + i + 1), xb, mb);
-        tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, da, xa, ma, pa, false, lane, tot_l, sum8_buf);
+        tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, da, xa, ma, pa, false, lane, tot_l, sum8_buf, stage, span.of0);
         if (kDemand && lane_in(readlane64(me.mask, 8 * c + i))) wd += da;
         if (i + 2 < 8) {
           sa = own_sigma(dat, me, 8 * c + i + 2);
           da = own_demand<kDemand>(dem, gv.dem_ld, u0, me, 8 * c + i + 2, lane);
           pa = gather8(cf, tile, i + 2, readlane64(me.mask, 8 * c + i + 2), xa, ma);
         }
-        tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, db, xb, mb, pb, false, lane, tot_l, sum8_buf);
+        tot_l = bwd_finish(cf, me, 8 * c + i + 1, i + 1, sb, db, xb, mb, pb, false, lane, tot_l, sum8_buf, stage, span.of0);
         if (kDemand && lane_in(readlane64(me.mask, 8 * c + i + 1))) wd += db;
       }
       const uint64_t mu_lane = shfl64(me.mask, 8 * c + (lane >> 3));
@@ -825,9 +838,14 @@ bwd_rows(const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ out_co
           pa = gather8(cf, extra, i, readlane64(me.mask, 8 * c + i), xa, ma);
           if (pa == 0) continue;
           sa = own_sigma(dat, me, 8 * c + i);
-          tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, 1.0, xa, ma, pa, true, lane, tot_l, sum8_buf);
+          tot_l = bwd_finish(cf, me, 8 * c + i, i, sa, 1.0, xa, ma, pa, true, lane, tot_l, sum8_buf, stage, span.of0);
         }
         if (qe >= 0 && (extra.mask & mu_lane) != 0) unsafeAtomicAdd(&pt[qe], tot_l);
+      }
+      if (stage != nullptr) {
+        __builtin_amdgcn_wave_barrier();
+        store_staged(cf, stage, span, lane);
+        __builtin_amdgcn_wave_barrier();
       }
     }
     tile = tile_next;
@@ -1568,7 +1586,7 @@ k_fwd(const int32_t* __restrict__ in_ptr, const int32_t* __restrict__ in_col, Gr
 template <typename TS>
 __host__ __device__ constexpr int bwd_wave_doubles() {
   constexpr int kSpreadDoubles = 8 * kWave + 8 * kWave * (int)sizeof(TS) / 8;
-  return kSpreadDoubles > kSum8Doubles ? kSpreadDoubles : kSum8Doubles;
+  return kSpreadDoubles > kBwdDoubles ? kSpreadDoubles : kBwdDoubles;
 }
 template <typename TS, bool kDemand>
 __device__ __forceinline__ void
