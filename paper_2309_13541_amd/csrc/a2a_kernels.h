@@ -204,8 +204,10 @@ __device__ __forceinline__ T group_sum8(const T (&x)[8], int lane) {
 // go through the LDS pipeline.  `buf` is this wave's kSum8Doubles doubles of LDS.
 constexpr int kSum8Row = kWave + 1;
 constexpr int kSum8Doubles = 8 * kSum8Row;
-// LDS of a wave of the backward kernel: 8 KB.  Rows layout: the eight sums, then the staged coef rows of a tile.
-constexpr int kBwdDoubles = 16 * kWave;
+// LDS of a wave of the backward kernel: 7.5 KB (30 KB per workgroup: five workgroups per compute unit, which is
+// what the registers allow; with 32 KB only four fit).  Rows layout: the eight sums, then the staged coef rows
+// of a tile.
+constexpr int kBwdDoubles = 15 * kWave;
 constexpr int kStageDoubles = kBwdDoubles - kSum8Doubles;
 __device__ __forceinline__ double wave_sum8_lds(const double (&x)[8], int lane, double* buf) {
 #pragma unroll
