@@ -1683,7 +1683,7 @@ k_extract_dist(GroupView gv, int tiles, int depth, int32_t* __restrict__ dist,
   const int row0 = (gv.batch0 + g) * 64;
   const int cnt = min(64, gv.src_count - row0);
   if (dist != nullptr && v < gv.N) {
-    for (int j = 0; j < cnt; ++j) dist[(size_t)(row0 + j) * gv.N + v] = t_d[j][t];
+    for (int j = 0; j < cnt; ++j) __builtin_nontemporal_store(t_d[j][t], &dist[(size_t)(row0 + j) * gv.N + v]);
   }
   if (dist_sum != nullptr && t < cnt) {
     long long s = 0;
@@ -1741,7 +1741,8 @@ k_extract_dist_planes(GroupView gv, int depth, int planes, int32_t* __restrict__
         if (dist_sum != nullptr) s += (long long)__popcll(__ballot(bit != 0 && live)) << p;
       }
     }
-    if (dist != nullptr && live) dist[(size_t)(row0 + j) * gv.N + v] = ((R >> j) & 1ull) ? d : -1;
+    if (dist != nullptr && live)
+      __builtin_nontemporal_store(((R >> j) & 1ull) ? d : -1, &dist[(size_t)(row0 + j) * gv.N + v]);
     if (lane == j) mine = s;
   }
   if (dist_sum != nullptr && lane < cnt && mine != 0)
@@ -1807,7 +1808,7 @@ k_extract_dist_packed(GroupView gv, int depth, int32_t* __restrict__ dist, long 
         if (j0 + e < cnt) {  // the same in all lanes; false only in a call's last, ragged batch
           int32_t* __restrict__ row = dist + (size_t)(row0 + j0 + e) * (size_t)gv.N;
           const int d = __builtin_amdgcn_sbfe((int)(e < 4 ? wlo : whi), 8 * (e & 3), 8);
-          if (live) row[v] = d;
+          if (live) __builtin_nontemporal_store(d, &row[v]);  // written once, not read here: keep the masks in L2
         }
       }
     }
@@ -1855,7 +1856,8 @@ k_extract_sigma(GroupView gv, int tiles, int depth, double* __restrict__ sigma_o
   const int row0 = (gv.batch0 + g) * 64;
   const int cnt = min(64, gv.src_count - row0);
   if (v0 + t < gv.N) {
-    for (int j = 0; j < cnt; ++j) sigma_out[(size_t)(row0 + j) * gv.N + v0 + t] = t_s[j][t];
+    for (int j = 0; j < cnt; ++j)
+      __builtin_nontemporal_store(t_s[j][t], &sigma_out[(size_t)(row0 + j) * gv.N + v0 + t]);
   }
 }
 
